@@ -1,0 +1,194 @@
+"""Pins for the CPU oracle: every check compares it with something that is not the oracle
+(a library GEMM on the densified matrix, closed forms, exact special cases, a hand-worked
+fixture), chosen so that a dropped term, a wrong index, a swapped operand or a transposed
+read in the oracle fails at least one of them."""
+import os
+
+import numpy as np
+import pytest
+
+import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def densify(A, dtype=np.float64):
+    D = np.zeros((A.m, A.k), dtype=dtype)
+    for i in range(A.m):
+        s, e = A.row_offsets[i], A.row_offsets[i + 1]
+        np.add.at(D[i], A.column_indices[s:e], A.values[s:e].astype(dtype))
+    return D
+
+
+def read_golden(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, vals = line.split(":")
+            out[key] = np.array([float(x) for x in vals.split()])
+    return out
+
+
+def test_hand_worked_example(oracle_lib):
+    g = read_golden("hand_worked_3x3.txt")
+    ro = g["row_offsets"].astype(np.int32)
+    ci = g["column_indices"].astype(np.int32)
+    C, S = oracle_lib.spmm(3, 3, 2, ro, ci, g["values"].astype(np.float32), g["B"].reshape(3, 2).astype(np.float32))
+    assert np.array_equal(C.ravel(), g["C"]) and np.array_equal(S.ravel(), g["S"])
+    out, oS = oracle_lib.sddmm(3, 3, 2, ro, ci, g["L"].reshape(3, 2).astype(np.float32),
+                               g["R"].reshape(3, 2).astype(np.float32))
+    assert np.array_equal(out, g["out"]) and np.array_equal(oS, g["outS"])
+
+
+@pytest.mark.parametrize("m,k,n,density,seed", [(17, 23, 9, 0.3, 1), (64, 40, 33, 0.5, 2), (5, 7, 1, 0.9, 3)])
+def test_spmm_equals_dense_gemm_small(oracle_lib, m, k, n, density, seed):
+    A = wl.uniform_mask_csr(m, k, density, seed)
+    B = wl.dense(k, n, seed + 100)
+    C, S = oracle_lib.spmm(m, k, n, A.row_offsets, A.column_indices, A.values, B)
+    D = densify(A)
+    ref = D @ B.astype(np.float64)                      # library GEMM, non-square, non-symmetric
+    assert np.allclose(C, ref, rtol=1e-12, atol=1e-12)
+    refS = np.abs(D) @ np.abs(B.astype(np.float64))
+    assert np.allclose(S, refS, rtol=1e-12, atol=1e-12)
+
+
+def test_spmm_equals_dense_gemm_config1(oracle_lib):
+    w = wl.tiny()
+    A = w["A"]
+    C, S = oracle_lib.spmm(A.m, A.k, w["n"], A.row_offsets, A.column_indices, A.values, w["B"])
+    ref = densify(A) @ w["B"].astype(np.float64)
+    assert np.allclose(C, ref, rtol=1e-11, atol=1e-11)
+    assert np.all(S >= np.abs(C) - 1e-9)
+
+
+def test_spmm_identity_and_permutation_are_exact(oracle_lib):
+    m = 37
+    rng = np.random.default_rng(5)
+    B = wl.dense(m, 19, 6)
+    ro = np.arange(m + 1, dtype=np.int32)
+    ones = np.ones(m, dtype=np.float32)
+    C, S = oracle_lib.spmm(m, m, 19, ro, np.arange(m, dtype=np.int32), ones, B)
+    assert np.array_equal(C, B.astype(np.float64))
+    perm = rng.permutation(m).astype(np.int32)
+    C, _ = oracle_lib.spmm(m, m, 19, ro, perm, ones, B)
+    assert np.array_equal(C, B[perm].astype(np.float64))          # row i of C is row perm[i] of B
+    scale = rng.standard_normal(m).astype(np.float32)
+    C, S = oracle_lib.spmm(m, m, 19, ro, perm, scale, B)
+    assert np.array_equal(C, scale.astype(np.float64)[:, None] * B[perm].astype(np.float64))
+    assert np.array_equal(S, np.abs(C))
+
+
+def test_spmm_all_ones_closed_form_and_empty_rows(oracle_lib):
+    A = wl.adversarial_csr(60, 80, 11)
+    A.values[:] = 1.0
+    B = np.ones((80, 7), dtype=np.float32)
+    C, S = oracle_lib.spmm(A.m, A.k, 7, A.row_offsets, A.column_indices, A.values, B)
+    lens = A.row_lengths.astype(np.float64)
+    assert np.array_equal(C, np.repeat(lens[:, None], 7, axis=1))
+    assert np.array_equal(S, C)
+    assert (lens == 0).sum() >= 3 and np.all(C[lens == 0] == 0.0)
+
+
+def test_spmm_linearity_and_column_independence(oracle_lib):
+    A = wl.uniform_mask_csr(40, 50, 0.3, 21)
+    B = wl.dense(50, 12, 22)
+    C, _ = oracle_lib.spmm(40, 50, 12, A.row_offsets, A.column_indices, A.values, B)
+    C2, _ = oracle_lib.spmm(40, 50, 12, A.row_offsets, A.column_indices, A.values * np.float32(2), B)
+    assert np.array_equal(C2, 2.0 * C)
+    B3 = B.copy()
+    B3[:, 5] = 0.0
+    C3, _ = oracle_lib.spmm(40, 50, 12, A.row_offsets, A.column_indices, A.values, B3)
+    keep = [j for j in range(12) if j != 5]
+    assert np.array_equal(C3[:, keep], C[:, keep]) and np.all(C3[:, 5] == 0.0)
+
+
+def test_spmm_unsorted_and_duplicate_columns(oracle_lib):
+    # duplicates are summed, order inside a row does not matter (up to rounding in double)
+    ro = np.array([0, 4, 4, 6], dtype=np.int32)
+    ci = np.array([3, 0, 3, 1, 2, 2], dtype=np.int32)
+    va = np.array([1, 2, 4, 8, 16, 32], dtype=np.float32)
+    B = wl.dense(4, 5, 31)
+    C, _ = oracle_lib.spmm(3, 4, 5, ro, ci, va, B)
+    D = np.zeros((3, 4))
+    D[0, 3] = 5; D[0, 0] = 2; D[0, 1] = 8; D[2, 2] = 48
+    assert np.allclose(C, D @ B.astype(np.float64), rtol=1e-13, atol=1e-13)
+
+
+def test_sddmm_full_mask_equals_dense_product(oracle_lib):
+    m, k, n = 13, 21, 10
+    L = wl.dense(m, n, 41)
+    R = wl.dense(k, n, 42)
+    ro = (np.arange(m + 1) * k).astype(np.int32)
+    ci = np.tile(np.arange(k, dtype=np.int32), m)
+    out, S = oracle_lib.sddmm(m, k, n, ro, ci, L, R)
+    ref = L.astype(np.float64) @ R.astype(np.float64).T            # library GEMM with transposed RHS
+    assert np.allclose(out.reshape(m, k), ref, rtol=1e-12, atol=1e-12)
+    refS = np.abs(L.astype(np.float64)) @ np.abs(R.astype(np.float64)).T
+    assert np.allclose(S.reshape(m, k), refS, rtol=1e-12, atol=1e-12)
+
+
+def test_sddmm_sampled_positions_and_closed_forms(oracle_lib):
+    A = wl.adversarial_csr(50, 64, 51)
+    n = 24
+    L = wl.dense(50, n, 52)
+    R = wl.dense(64, n, 53)
+    out, S = oracle_lib.sddmm(50, 64, n, A.row_offsets, A.column_indices, L, R)
+    full = L.astype(np.float64) @ R.astype(np.float64).T
+    rows = np.repeat(np.arange(50), A.row_lengths)
+    assert np.allclose(out, full[rows, A.column_indices], rtol=1e-12, atol=1e-12)
+    ones_out, ones_S = oracle_lib.sddmm(50, 64, n, A.row_offsets, A.column_indices,
+                                        np.ones((50, n), np.float32), np.ones((64, n), np.float32))
+    assert np.all(ones_out == n) and np.all(ones_S == n)
+
+
+def test_sddmm_spmm_adjoint_identity(oracle_lib):
+    # <SDDMM(L,R), v> == <L, SpMM(A_v, R)> for any values v on the topology
+    A = wl.uniform_mask_csr(33, 45, 0.25, 61)
+    n = 17
+    L = wl.dense(33, n, 62)
+    R = wl.dense(45, n, 63)
+    out, _ = oracle_lib.sddmm(33, 45, n, A.row_offsets, A.column_indices, L, R)
+    C, _ = oracle_lib.spmm(33, 45, n, A.row_offsets, A.column_indices, A.values, R)
+    lhs = float(np.dot(out, A.values.astype(np.float64)))
+    rhs = float(np.sum(L.astype(np.float64) * C))
+    assert abs(lhs - rhs) <= 1e-10 * max(1.0, abs(lhs))
+
+
+def test_fp16_decode_is_exact_for_every_finite_half(oracle_lib):
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    halves = bits.view(np.float16)
+    finite = np.isfinite(halves)
+    vals = halves[finite]
+    k = vals.shape[0]
+    B = vals.reshape(k, 1)
+    ro = np.arange(k + 1, dtype=np.int32)
+    C, S = oracle_lib.spmm(k, k, 1, ro, np.arange(k, dtype=np.int32), np.ones(k, np.float16), B)
+    assert np.array_equal(C.ravel(), vals.astype(np.float64))       # numpy's own half -> double
+    assert np.array_equal(S.ravel(), np.abs(vals.astype(np.float64)))
+
+
+def test_fp16_ops_match_dense_products(oracle_lib):
+    A = wl.uniform_mask_csr(20, 30, 0.4, 71)
+    A.values = A.values.astype(np.float16)
+    B = wl.dense(30, 11, 72, np.float16)
+    C, _ = oracle_lib.spmm(20, 30, 11, A.row_offsets, A.column_indices, A.values, B)
+    assert np.allclose(C, densify(A) @ B.astype(np.float64), rtol=1e-12, atol=1e-12)
+    L = wl.dense(20, 11, 73, np.float16)
+    out, _ = oracle_lib.sddmm(20, 30, 11, A.row_offsets, A.column_indices, L, B)
+    full = L.astype(np.float64) @ B.astype(np.float64).T
+    rows = np.repeat(np.arange(20), A.row_lengths)
+    assert np.allclose(out, full[rows, A.column_indices], rtol=1e-12, atol=1e-12)
+
+
+def test_row_order_is_stable_descending_permutation(oracle_lib):
+    A = wl.lognormal_rows_csr(300, 128, 0.2, 81)
+    order = oracle_lib.row_order(A.m, A.row_offsets)
+    lens = A.row_lengths
+    assert sorted(order.tolist()) == list(range(A.m))
+    assert np.all(np.diff(lens[order]) <= 0)
+    same = np.diff(lens[order]) == 0
+    assert np.all(np.diff(order)[same] > 0)                          # ties: ascending row index
+    assert np.array_equal(order, np.argsort(-lens, kind="stable"))  # library stable sort
