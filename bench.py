@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of libspdl on one MI355X.
+
+One step = one pass of the whole hot path over the weight-sparse LSTM workload: for each
+sparsity in {70,80,90,95,98} % one SpMM (forward, A 8192x10240, B 10240x128) and one SDDMM
+(weight gradient, L 8192x128, R 10240x128) on the same topology: ten kernel launches through
+the C ABI, inputs resident in HBM, row orders built beforehand (a per-topology one-off).
+
+Prints ONE JSON line.  value = useful GFLOP/s = sum(2*nnz*n) / time.  Extra fields give the
+per-case times, the roofline of the dominant kernel (HIP events around every launch inside
+the timed region) and the CPU oracle timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP32_VECTOR_PEAK_TFLOPS = 157.3      # 256 CUs x 2.4 GHz x 256 flop/clk/CU (published)
+HBM_PEAK_GBS = 8000.0
+
+
+def spmm_bytes(m, k, n, nnz, eb=4):
+    return nnz * (eb + 4) + (m + 1) * 4 + m * 4 + k * n * eb + m * n * eb
+
+
+def sddmm_bytes(m, k, n, nnz, eb=4):
+    return nnz * 4 + (m + 1) * 4 + m * n * eb + k * n * eb + nnz * eb
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+class Case:
+    """One (operation, problem) pair with its device buffers and a launch closure."""
+
+    def __init__(self, name, op, A, n, dense_ops, spdl, torch, f16=False):
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        self.name, self.op, self.n = name, op, n
+        self.m, self.k, self.nnz = A.m, A.k, A.nnz
+        self.flops = 2.0 * A.nnz * n
+        eb = 2 if f16 else 4
+        self.bytes = (spmm_bytes if op == "spmm" else sddmm_bytes)(A.m, A.k, n, A.nnz, eb)
+        ro, ci = dev(A.row_offsets), dev(A.column_indices)
+        dt = torch.float16 if f16 else torch.float32
+        if op == "spmm":
+            val = dev(A.values)
+            order = dev(spdl.spdl_build_row_order(A.m, A.row_offsets))
+            B = dev(dense_ops[0])
+            C = torch.empty((A.m, n), dtype=dt, device="cuda")
+            fn = spdl.spdl_spmm_f16 if f16 else spdl.spdl_spmm
+            self.launch = lambda: fn(A.m, A.k, n, A.nnz, ro, ci, val, order, B, C)
+            self.info = spdl.spdl_select_spmm(A.m, A.k, n, A.nnz, eb, B, C)
+        else:
+            L, R = dev(dense_ops[0]), dev(dense_ops[1])
+            out = torch.empty(A.nnz, dtype=dt, device="cuda")
+            fn = spdl.spdl_sddmm_f16 if f16 else spdl.spdl_sddmm
+            self.launch = lambda: fn(A.m, A.k, n, A.nnz, ro, ci, L, R, out)
+            self.info = spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, eb, L, R)
+        self.kernel = spdl.spdl_variant_name(0 if op == "spmm" else 1, self.info["variant"])
+        self.ms = []
+
+    def report(self):
+        t = float(np.mean(self.ms)) * 1e-3
+        return {
+            "case": self.name, "op": self.op, "kernel": self.kernel, "nnz": self.nnz,
+            "us": round(t * 1e6, 2), "us_min": round(float(np.min(self.ms)) * 1e3, 2),
+            "gflops": round(self.flops / t / 1e9, 1), "eff_GBs": round(self.bytes / t / 1e9, 1),
+            "frac_fp32_peak": round(self.flops / t / 1e12 / FP32_VECTOR_PEAK_TFLOPS, 4),
+            "frac_hbm_peak": round(self.bytes / t / 1e9 / HBM_PEAK_GBS, 4),
+        }
+
+
+def time_cases(cases, steps, warmup, torch):
+    """Warm up, then time `steps` passes over `cases`: wall clock around the whole region and a
+    HIP event pair (on the launch stream) around every launch."""
+    for _ in range(warmup):
+        for c in cases:
+            c.launch()
+    torch.cuda.synchronize()
+    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in cases] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        for c, (e0, e1) in zip(cases, events[s]):
+            e0.record()
+            c.launch()
+            e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    for c in cases:
+        c.ms = []
+    for s in range(steps):
+        for c, (e0, e1) in zip(cases, events[s]):
+            c.ms.append(e0.elapsed_time(e1))
+    return wall
+
+
+def cpu_baseline(lstm90, oracle):
+    """The oracle as it stands, on this machine's host cores, on a bounded sample of the
+    workload: SpMM + SDDMM of the 90 %-sparse LSTM problem (one of the step's five)."""
+    A, n = lstm90["A"], lstm90["n"]
+    oracle.spmm(64, A.k, n, A.row_offsets[:65], A.column_indices, A.values, lstm90["B"])   # page in
+    t0 = time.perf_counter()
+    oracle.spmm(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, lstm90["B"])
+    oracle.sddmm(A.m, A.k, n, A.row_offsets, A.column_indices, lstm90["L"], lstm90["R"])
+    dt = time.perf_counter() - t0
+    return {"value": round(2 * 2.0 * A.nnz * n / dt / 1e9, 2), "unit": "GFLOP/s",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "SpMM + SDDMM of the LSTM problem at 90 % sparsity (nnz=%d, n=128), fp64 "
+                      "accumulation plus the |product| scale, %.2f s" % (A.nnz, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-extra", action="store_true", help="skip the Transformer/attention/conv report")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--only", default="", help="comma list of LSTM sparsities to run (profiling aid)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU path exists")
+
+    import torch
+    import paper_2006_10901_amd as spdl
+    import workloads as wl
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    spdl.lib()
+
+    sparsities = [int(s) for s in args.only.split(",")] if args.only else list(wl.LSTM_SPARSITIES)
+    cases, lstm90 = [], None
+    for sp in sparsities:
+        t0 = time.time()
+        w = wl.lstm(sp)
+        if sp == 90:
+            lstm90 = w
+        cases.append(Case(f"lstm{sp}", "spmm", w["A"], 128, (w["B"],), spdl, torch))
+        cases.append(Case(f"lstm{sp}", "sddmm", w["A"], 128, (w["L"], w["R"]), spdl, torch))
+        log(f"[bench] lstm {sp}%: nnz={w['A'].nnz} generated+uploaded in {time.time() - t0:.1f}s")
+
+    wall = time_cases(cases, args.steps, args.warmup, torch)
+    ms_per_step = wall / args.steps * 1e3
+    step_flops = sum(c.flops for c in cases)
+    value = step_flops / (wall / args.steps) / 1e9
+    log(f"[bench] {args.steps} steps, {ms_per_step:.3f} ms/step, {value:.0f} GFLOP/s")
+
+    # dominant kernel = the kernel family with the largest share of event time
+    by_kernel = {}
+    for c in cases:
+        d = by_kernel.setdefault((c.op, c.kernel), {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0})
+        d["ms"] += float(np.sum(c.ms)); d["flops"] += c.flops * len(c.ms)
+        d["bytes"] += c.bytes * len(c.ms); d["launches"] += len(c.ms)
+    (dom_op, dom_kernel), dom = max(by_kernel.items(), key=lambda kv: kv[1]["ms"])
+    achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+    roofline = {
+        "bound": "alu", "achieved": round(achieved, 3), "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+        "frac": round(achieved / FP32_VECTOR_PEAK_TFLOPS, 4), "traffic": None,
+        "kernel": f"{dom_op}_{dom_kernel}", "avg_launch_us": round(dom["ms"] / dom["launches"] * 1e3, 2),
+        "flops_per_launch": dom["flops"] / dom["launches"],
+        "eff_GBs": round(dom["bytes"] / (dom["ms"] * 1e-3) / 1e9, 1),
+        "frac_hbm_peak": round(dom["bytes"] / (dom["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+    }
+
+    result = {
+        "metric": "SpMM & SDDMM useful GFLOP/s (2*nnz*n), 1 MI355X", "value": round(value, 1),
+        "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "weight-sparse LSTM SpMM + SDDMM fp32, A 8192x10240, n=128, "
+                               "sparsity sweep " + "/".join(str(s) for s in sparsities) + " %, uniform mask"},
+        "roofline": roofline,
+        "cases": [c.report() for c in cases],
+    }
+
+    if not args.no_extra:
+        extra = []
+        for which in (1, 2):
+            w = wl.transformer_ffn(which)
+            extra.append(Case(f"ffn_W{which}", "spmm", w["A"], 4096, (w["B"],), spdl, torch))
+            extra.append(Case(f"ffn_W{which}", "sddmm", w["A"], 4096, (w["L"], w["R"]), spdl, torch))
+        w = wl.attention(0)
+        extra.append(Case("attention_head", "sddmm", w["A"], 64, (w["Q"], w["K"]), spdl, torch))
+        extra.append(Case("attention_head", "spmm", w["A"], 64, (w["V"],), spdl, torch))
+        for skew in (False, True):
+            w = wl.conv1x1(skew)
+            nm = "conv1x1_f16_skewed" if skew else "conv1x1_f16"
+            extra.append(Case(nm, "spmm", w["A"], 3136, (w["B"],), spdl, torch, f16=True))
+            extra.append(Case(nm, "sddmm", w["A"], 3136, (w["L"], w["R"]), spdl, torch, f16=True))
+        time_cases(extra, max(5, args.steps // 2), 2, torch)
+        result["other_configs"] = [c.report() for c in extra]
+        ffn = [c for c in extra if c.name.startswith("ffn")]
+        t = sum(float(np.mean(c.ms)) for c in ffn) * 1e-3
+        result["transformer_ffn_gflops"] = round(sum(c.flops for c in ffn) / t / 1e9, 1)
+
+    if not args.no_cpu:
+        import oracle
+        if lstm90 is None:
+            lstm90 = wl.lstm(90)
+        result["cpu_baseline"] = cpu_baseline(lstm90, oracle)
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,106 @@
+/*
+ * libspdl -- CSR SpMM and SDDMM for deep-learning sparsity on AMD gfx950 (MI355X).
+ *
+ * C ABI.  Every pointer is marked HOST or DEVICE.  The library never allocates, frees or
+ * keeps a caller's pointer, and never writes an input array.  Kernels are enqueued on
+ * `stream` (a hipStream_t passed as void*; NULL = the default stream) with no host
+ * synchronisation.  Every function returns an spdl_status and never throws, aborts or
+ * prints.
+ *
+ * Common conventions
+ *   A is an m x k sparse matrix in the standard compressed-sparse-row format
+ *   (paper Sec. "Data Organization"):
+ *     row_offsets     int32[m+1], row_offsets[0] == 0, non-decreasing, row_offsets[m] == nnz
+ *     column_indices  int32[nnz], each in [0,k); any order inside a row (duplicates allowed:
+ *                     SpMM sums them, SDDMM produces one output per stored entry).  Rows with
+ *                     ascending indices take the fastest path.
+ *     values          [nnz]
+ *   Dense matrices are row-major with no padding (leading dimension == number of columns).
+ *   Sizes: m, k, n, nnz >= 0 and m*n, k*n < 2^31.  m == 0, n == 0 and nnz == 0 are valid.
+ *   Base pointers must be aligned to their element type; 16-byte aligned bases and n % 4 == 0
+ *   (n % 8 == 0 for fp16) select the widest vector path, anything else a narrower one.
+ */
+#ifndef SPDL_H_
+#define SPDL_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SPDL_OK = 0,
+  SPDL_ERR_INVALID = -1,      /* negative size, null required pointer, size overflow          */
+  SPDL_ERR_LAUNCH = -2,       /* the HIP runtime refused a launch (hipGetLastError != success) */
+  SPDL_ERR_BAD_CSR = -3,      /* spdl_validate_csr_host: arrays are not a valid CSR topology   */
+  SPDL_ERR_UNSUPPORTED = -4   /* a forced kernel variant cannot run this problem              */
+} spdl_status;
+
+/* SpMM:  C = A B.   (paper Sec. "Sparse Matrix--Matrix Multiplication Operation")
+ *   C[i,j] = sum over stored entries p of row i of values[p] * B[column_indices[p], j].
+ *   row_offsets, column_indices, values : DEVICE, CSR of A (m x k, nnz entries), fp32 values
+ *   row_order : DEVICE int32[m], a permutation of [0,m) giving the order in which rows are
+ *               handed to workgroups (paper Sec. "Row Swizzle Load Balancing"); NULL = identity.
+ *               The result does not depend on it.
+ *   B : DEVICE fp32[k*n];   C : DEVICE fp32[m*n], fully overwritten (empty rows become +0).
+ *   fp32 fused multiply-add accumulation in the stored order of each row. */
+int spdl_spmm(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+              const float* values, const int* row_order, const float* B, float* C, void* stream);
+
+/* SDDMM:  out = (L R^T) sampled at A's stored positions, without scaling by A's values.
+ *   (paper Sec. "Sampled Dense--Dense Matrix Multiplication Operation")
+ *   out_values[p] = sum_j L[i,j] * R[column_indices[p], j] for every entry p of row i.
+ *   row_offsets, column_indices : DEVICE, topology of A (m x k)
+ *   L : DEVICE fp32[m*n];  R : DEVICE fp32[k*n];  out_values : DEVICE fp32[nnz], CSR order,
+ *   fully overwritten.  out_values may be the array that holds A's values (they are not read). */
+int spdl_sddmm(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+               const float* L, const float* R, float* out_values, void* stream);
+
+/* Mixed precision (paper Sec. "Mixed Precision"): operands and results are IEEE binary16
+ * (passed as uint16_t bit patterns), every product and sum is fp32, results are rounded to
+ * binary16 once (round to nearest even).  Column indices stay int32. */
+int spdl_spmm_f16(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                  const uint16_t* values, const int* row_order, const uint16_t* B, uint16_t* C,
+                  void* stream);
+int spdl_sddmm_f16(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                   const uint16_t* L, const uint16_t* R, uint16_t* out_values, void* stream);
+
+/* Row swizzle (paper Sec. "Row Binning & Row Bundling Heuristics"): row indices sorted by
+ * decreasing row length, equal lengths in ascending row index.  Pure host code.
+ *   row_offsets_host : HOST int32[m+1];   row_order_host : HOST int32[m], written. */
+int spdl_build_row_order(int m, const int* row_offsets_host, int* row_order_host);
+
+/* Host-side check of a CSR topology: offsets start at 0, never decrease, end at nnz; every
+ * column index lies in [0,k).  Returns SPDL_OK or SPDL_ERR_BAD_CSR.  If sorted_out is not
+ * NULL it receives 1 when every row's indices are strictly ascending, else 0.
+ *   row_offsets_host : HOST int32[m+1];  column_indices_host : HOST int32[nnz]. */
+int spdl_validate_csr_host(int m, int k, int nnz, const int* row_offsets_host,
+                           const int* column_indices_host, int* sorted_out);
+
+/* Kernel selection (paper Sec. "Experiments", first paragraph: tile sizes and vector widths
+ * are picked from the problem shape).  spdl_select_* report what the dispatcher would launch;
+ * spdl_force_variant overrides it for ablation runs (variant < 0 restores the heuristic).
+ * The variant ids are listed by spdl_variant_name. */
+typedef struct {
+  int variant;          /* kernel family id                                        */
+  int vec;              /* elements per lane per memory instruction                */
+  int lanes_per_row;    /* lanes cooperating on one output row / one dot product   */
+  int rows_per_block;   /* sparse rows (SpMM) or nonzero strips (SDDMM) per block  */
+  int block_threads;
+  int grid_x, grid_y;
+} spdl_launch_info;
+int spdl_select_spmm(int m, int k, int n, int nnz, int elem_bytes, const void* B, const void* C,
+                     spdl_launch_info* info);
+int spdl_select_sddmm(int m, int k, int n, int nnz, int elem_bytes, const void* L, const void* R,
+                      spdl_launch_info* info);
+int spdl_force_variant(int op /*0 = SpMM, 1 = SDDMM*/, int variant);
+const char* spdl_variant_name(int op, int variant);   /* NULL if no such variant */
+
+const char* spdl_status_string(int status);
+int spdl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif  /* SPDL_H_ */

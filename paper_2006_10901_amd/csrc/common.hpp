@@ -1,0 +1,80 @@
+// Shared device helpers for the libspdl kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spdl {
+
+constexpr int kWave = 64;
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// VEC consecutive elements of T, moved with one memory instruction and widened to fp32.
+template <typename T, int VEC> struct Pack;
+
+template <> struct Pack<float, 1> {
+  static __device__ __forceinline__ void load(const float* p, float (&x)[1]) { x[0] = *p; }
+  static __device__ __forceinline__ void store(float* p, const float (&x)[1]) { *p = x[0]; }
+};
+template <> struct Pack<float, 2> {
+  static __device__ __forceinline__ void load(const float* p, float (&x)[2]) {
+    f32x2 v = *reinterpret_cast<const f32x2*>(p); x[0] = v.x; x[1] = v.y;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&x)[2]) {
+    f32x2 v = {x[0], x[1]}; *reinterpret_cast<f32x2*>(p) = v;
+  }
+};
+template <> struct Pack<float, 4> {
+  static __device__ __forceinline__ void load(const float* p, float (&x)[4]) {
+    f32x4 v = *reinterpret_cast<const f32x4*>(p); x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&x)[4]) {
+    f32x4 v = {x[0], x[1], x[2], x[3]}; *reinterpret_cast<f32x4*>(p) = v;
+  }
+};
+template <> struct Pack<_Float16, 1> {
+  static __device__ __forceinline__ void load(const _Float16* p, float (&x)[1]) { x[0] = (float)*p; }
+  static __device__ __forceinline__ void store(_Float16* p, const float (&x)[1]) { *p = (_Float16)x[0]; }
+};
+template <> struct Pack<_Float16, 2> {
+  static __device__ __forceinline__ void load(const _Float16* p, float (&x)[2]) {
+    f16x2 v = *reinterpret_cast<const f16x2*>(p); x[0] = (float)v.x; x[1] = (float)v.y;
+  }
+  static __device__ __forceinline__ void store(_Float16* p, const float (&x)[2]) {
+    f16x2 v = {(_Float16)x[0], (_Float16)x[1]}; *reinterpret_cast<f16x2*>(p) = v;
+  }
+};
+template <> struct Pack<_Float16, 4> {
+  static __device__ __forceinline__ void load(const _Float16* p, float (&x)[4]) {
+    f16x4 v = *reinterpret_cast<const f16x4*>(p);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x[i] = (float)v[i];
+  }
+  static __device__ __forceinline__ void store(_Float16* p, const float (&x)[4]) {
+    f16x4 v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = (_Float16)x[i];
+    *reinterpret_cast<f16x4*>(p) = v;
+  }
+};
+template <> struct Pack<_Float16, 8> {
+  static __device__ __forceinline__ void load(const _Float16* p, float (&x)[8]) {
+    f16x8 v = *reinterpret_cast<const f16x8*>(p);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = (float)v[i];
+  }
+  static __device__ __forceinline__ void store(_Float16* p, const float (&x)[8]) {
+    f16x8 v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (_Float16)x[i];
+    *reinterpret_cast<f16x8*>(p) = v;
+  }
+};
+
+__device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+}  // namespace spdl

@@ -1,0 +1,245 @@
+// libspdl: C ABI, argument checks, kernel selection and launches.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <atomic>
+#include <cstdint>
+#include <numeric>
+#include <vector>
+
+#include "../../include/spdl.h"
+#include "common.hpp"
+#include "sddmm_rowstrip.hpp"
+#include "spmm_rowsplit.hpp"
+
+namespace {
+
+using namespace spdl;
+
+enum SpmmVariant { kSpmmRowsplit = 0, kSpmmVariants };
+enum SddmmVariant { kSddmmRowstrip = 0, kSddmmVariants };
+
+std::atomic<int> g_forced[2] = {{-1}, {-1}};
+
+inline bool aligned(const void* p, size_t bytes) { return (reinterpret_cast<uintptr_t>(p) % bytes) == 0; }
+
+inline bool sizes_ok(int m, int k, int n, int nnz) {
+  if (m < 0 || k < 0 || n < 0 || nnz < 0) return false;
+  const int64_t lim = (int64_t)1 << 31;
+  return (int64_t)m * n < lim && (int64_t)k * n < lim;
+}
+
+// Widest vector width (in elements) usable for rows of length n starting at these bases.
+template <typename T>
+int pick_vec(int n, const void* a, const void* b, int max_vec) {
+  for (int v = max_vec; v > 1; v /= 2)
+    if (n % v == 0 && aligned(a, v * sizeof(T)) && aligned(b, v * sizeof(T))) return v;
+  return 1;
+}
+
+// Lanes per row: the smallest group whose tile covers n, so that small n spreads a wave over
+// several rows instead of idling lanes (paper Sec. "Subwarp Tiling").
+inline int pick_group(int n, int vec) {
+  for (int g = 8; g < kWave; g *= 2)
+    if (g * vec >= n) return g;
+  return kWave;
+}
+
+template <typename T>
+void fill_spmm_info(int m, int n, const void* B, const void* C, spdl_launch_info* info) {
+  const int vec = pick_vec<T>(n, B, C, 16 / (int)sizeof(T));
+  const int g = pick_group(n, vec);
+  info->variant = kSpmmRowsplit;
+  info->vec = vec;
+  info->lanes_per_row = g;
+  info->rows_per_block = 256 / g;
+  info->block_threads = 256;
+  info->grid_x = (m + info->rows_per_block - 1) / info->rows_per_block;
+  info->grid_y = (n + g * vec - 1) / (g * vec);
+}
+
+template <typename T, int VEC>
+int launch_spmm_rowsplit_g(const spdl_launch_info& li, int m, int n, const int* ro, const int* ci,
+                           const T* val, const int* order, const T* B, T* C, hipStream_t st) {
+  dim3 grid(li.grid_x, li.grid_y), block(256);
+  switch (li.lanes_per_row) {
+    case 8: spmm_rowsplit_kernel<T, VEC, 8><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C); break;
+    case 16: spmm_rowsplit_kernel<T, VEC, 16><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C); break;
+    case 32: spmm_rowsplit_kernel<T, VEC, 32><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C); break;
+    case 64: spmm_rowsplit_kernel<T, VEC, 64><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C); break;
+    default: return SPDL_ERR_INVALID;
+  }
+  return SPDL_OK;
+}
+
+template <typename T>
+int launch_spmm_rowsplit(const spdl_launch_info& li, int m, int n, const int* ro, const int* ci,
+                         const T* val, const int* order, const T* B, T* C, hipStream_t st) {
+  switch (li.vec) {
+    case 1: return launch_spmm_rowsplit_g<T, 1>(li, m, n, ro, ci, val, order, B, C, st);
+    case 2: return launch_spmm_rowsplit_g<T, 2>(li, m, n, ro, ci, val, order, B, C, st);
+    case 4: return launch_spmm_rowsplit_g<T, 4>(li, m, n, ro, ci, val, order, B, C, st);
+    case 8:
+      if constexpr (sizeof(T) == 2) return launch_spmm_rowsplit_g<T, 8>(li, m, n, ro, ci, val, order, B, C, st);
+      return SPDL_ERR_INVALID;
+    default: return SPDL_ERR_INVALID;
+  }
+}
+
+template <typename T>
+int spmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const T* val,
+              const int* order, const T* B, T* C, void* stream) {
+  if (!sizes_ok(m, k, n, nnz)) return SPDL_ERR_INVALID;
+  if (m == 0 || n == 0) return SPDL_OK;
+  if (!ro || !C || (nnz > 0 && (!ci || !val || !B))) return SPDL_ERR_INVALID;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  spdl_launch_info li;
+  fill_spmm_info<T>(m, n, B, C, &li);
+  (void)hipGetLastError();
+  int rc = launch_spmm_rowsplit<T>(li, m, n, ro, ci, val, order, B, C, st);
+  if (rc != SPDL_OK) return rc;
+  return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
+}
+
+template <typename T>
+void fill_sddmm_info(int m, int n, int nnz, const void* L, const void* R, spdl_launch_info* info) {
+  int vec = pick_vec<T>(n, L, R, 16 / (int)sizeof(T));
+  while (vec > 1 && kWave * vec / 2 >= n) vec /= 2;     // do not idle lanes on short dot products
+  const int avg = m > 0 ? nnz / m : 0;
+  const int split = std::max(1, std::min(8, avg / (4 * kStrip)));
+  info->variant = kSddmmRowstrip;
+  info->vec = vec;
+  info->lanes_per_row = kWave;
+  info->rows_per_block = split;             // waves sharing one sparse row
+  info->block_threads = 256;
+  const int64_t waves = (int64_t)m * split;
+  info->grid_x = (int)((waves + 3) / 4);
+  info->grid_y = 1;
+}
+
+template <typename T>
+int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const T* L, const T* R,
+               T* out, void* stream) {
+  if (!sizes_ok(m, k, n, nnz)) return SPDL_ERR_INVALID;
+  if (m == 0 || nnz == 0) return SPDL_OK;
+  if (!ro || !ci || !out || (n > 0 && (!L || !R))) return SPDL_ERR_INVALID;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  spdl_launch_info li;
+  fill_sddmm_info<T>(m, n, nnz, L, R, &li);
+  dim3 grid(li.grid_x), block(256);
+  const int split = li.rows_per_block;
+  (void)hipGetLastError();
+  switch (li.vec) {
+    case 1: sddmm_rowstrip_kernel<T, 1><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out); break;
+    case 2: sddmm_rowstrip_kernel<T, 2><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out); break;
+    case 4: sddmm_rowstrip_kernel<T, 4><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out); break;
+    case 8:
+      if constexpr (sizeof(T) == 2) {
+        sddmm_rowstrip_kernel<T, 8><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out);
+        break;
+      }
+      return SPDL_ERR_INVALID;
+    default: return SPDL_ERR_INVALID;
+  }
+  return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int spdl_spmm(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+              const float* values, const int* row_order, const float* B, float* C, void* stream) {
+  return spmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, values, row_order, B, C, stream);
+}
+
+int spdl_spmm_f16(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                  const uint16_t* values, const int* row_order, const uint16_t* B, uint16_t* C,
+                  void* stream) {
+  return spmm_impl<_Float16>(m, k, n, nnz, row_offsets, column_indices,
+                             reinterpret_cast<const _Float16*>(values), row_order,
+                             reinterpret_cast<const _Float16*>(B), reinterpret_cast<_Float16*>(C), stream);
+}
+
+int spdl_sddmm(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+               const float* L, const float* R, float* out_values, void* stream) {
+  return sddmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stream);
+}
+
+int spdl_sddmm_f16(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                   const uint16_t* L, const uint16_t* R, uint16_t* out_values, void* stream) {
+  return sddmm_impl<_Float16>(m, k, n, nnz, row_offsets, column_indices,
+                              reinterpret_cast<const _Float16*>(L), reinterpret_cast<const _Float16*>(R),
+                              reinterpret_cast<_Float16*>(out_values), stream);
+}
+
+int spdl_build_row_order(int m, const int* row_offsets_host, int* row_order_host) {
+  if (m < 0 || (m > 0 && (!row_offsets_host || !row_order_host))) return SPDL_ERR_INVALID;
+  std::iota(row_order_host, row_order_host + m, 0);
+  std::stable_sort(row_order_host, row_order_host + m, [&](int a, int b) {
+    return row_offsets_host[a + 1] - row_offsets_host[a] > row_offsets_host[b + 1] - row_offsets_host[b];
+  });
+  return SPDL_OK;
+}
+
+int spdl_validate_csr_host(int m, int k, int nnz, const int* ro, const int* ci, int* sorted_out) {
+  if (m < 0 || k < 0 || nnz < 0 || !ro || (nnz > 0 && !ci)) return SPDL_ERR_INVALID;
+  if (ro[0] != 0 || ro[m] != nnz) return SPDL_ERR_BAD_CSR;
+  int sorted = 1;
+  for (int i = 0; i < m; ++i) {
+    if (ro[i + 1] < ro[i] || ro[i + 1] > nnz) return SPDL_ERR_BAD_CSR;
+    for (int p = ro[i]; p < ro[i + 1]; ++p) {
+      if (ci[p] < 0 || ci[p] >= k) return SPDL_ERR_BAD_CSR;
+      if (p > ro[i] && ci[p] <= ci[p - 1]) sorted = 0;
+    }
+  }
+  if (sorted_out) *sorted_out = sorted;
+  return SPDL_OK;
+}
+
+int spdl_select_spmm(int m, int k, int n, int nnz, int elem_bytes, const void* B, const void* C,
+                     spdl_launch_info* info) {
+  if (!info || !sizes_ok(m, k, n, nnz) || (elem_bytes != 2 && elem_bytes != 4)) return SPDL_ERR_INVALID;
+  if (elem_bytes == 4) fill_spmm_info<float>(m, n, B, C, info);
+  else fill_spmm_info<_Float16>(m, n, B, C, info);
+  return SPDL_OK;
+}
+
+int spdl_select_sddmm(int m, int k, int n, int nnz, int elem_bytes, const void* L, const void* R,
+                      spdl_launch_info* info) {
+  if (!info || !sizes_ok(m, k, n, nnz) || (elem_bytes != 2 && elem_bytes != 4)) return SPDL_ERR_INVALID;
+  if (elem_bytes == 4) fill_sddmm_info<float>(m, n, nnz, L, R, info);
+  else fill_sddmm_info<_Float16>(m, n, nnz, L, R, info);
+  return SPDL_OK;
+}
+
+int spdl_force_variant(int op, int variant) {
+  if (op < 0 || op > 1) return SPDL_ERR_INVALID;
+  const int limit = op == 0 ? kSpmmVariants : kSddmmVariants;
+  if (variant >= limit) return SPDL_ERR_INVALID;
+  g_forced[op].store(variant < 0 ? -1 : variant);
+  return SPDL_OK;
+}
+
+const char* spdl_variant_name(int op, int variant) {
+  static const char* const spmm[] = {"rowsplit"};
+  static const char* const sddmm[] = {"rowstrip"};
+  if (op == 0 && variant >= 0 && variant < kSpmmVariants) return spmm[variant];
+  if (op == 1 && variant >= 0 && variant < kSddmmVariants) return sddmm[variant];
+  return nullptr;
+}
+
+const char* spdl_status_string(int status) {
+  switch (status) {
+    case SPDL_OK: return "ok";
+    case SPDL_ERR_INVALID: return "invalid argument";
+    case SPDL_ERR_LAUNCH: return "kernel launch failed";
+    case SPDL_ERR_BAD_CSR: return "not a valid CSR topology";
+    case SPDL_ERR_UNSUPPORTED: return "variant does not support this problem";
+    default: return "unknown status";
+  }
+}
+
+int spdl_version(void) { return 100; }
+
+}  // extern "C"

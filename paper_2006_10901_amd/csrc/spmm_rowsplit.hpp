@@ -1,0 +1,56 @@
+// SpMM, row-splitting family: a group of G lanes owns one sparse row and a 1-D tile of
+// G*VEC output columns (paper Sec. "Hierarchical 1-Dimensional Tiling" and "Subwarp Tiling").
+// Dense rows of B are gathered straight from global memory, one vector load per lane per
+// nonzero.  This is the general kernel: any n, any alignment, any column order inside a row.
+#pragma once
+#include "common.hpp"
+
+namespace spdl {
+
+template <typename T, int VEC, int G>
+__global__ __launch_bounds__(256) void spmm_rowsplit_kernel(
+    int m, int n, const int* __restrict__ row_offsets, const int* __restrict__ column_indices,
+    const T* __restrict__ values, const int* __restrict__ row_order, const T* __restrict__ B,
+    T* __restrict__ C) {
+  constexpr int ROWS = 256 / G;
+  constexpr int U = 8;
+  const int sub = threadIdx.x / G;
+  const int lane = threadIdx.x % G;
+  const int slot = blockIdx.x * ROWS + sub;
+  if (slot >= m) return;
+  int row = row_order ? row_order[slot] : slot;          // row swizzle: one extra load
+  if (G == kWave) row = uniform(row);                    // whole wave on one row: scalar loads
+  const int col = (blockIdx.y * G + lane) * VEC;
+  const bool active = col < n;
+  int p = row_offsets[row];
+  const int end = row_offsets[row + 1];
+  const T* Bcol = B + (active ? col : 0);
+
+  float acc[VEC];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+
+  for (; p + U <= end; p += U) {
+    float a[U];
+    int c[U];
+    float b[U][VEC];
+#pragma unroll
+    for (int u = 0; u < U; ++u) { a[u] = (float)values[p + u]; c[u] = column_indices[p + u]; }
+#pragma unroll
+    for (int u = 0; u < U; ++u) Pack<T, VEC>::load(Bcol + (size_t)c[u] * n, b[u]);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[v] = __builtin_fmaf(a[u], b[u][v], acc[v]);
+  }
+  for (; p < end; ++p) {
+    const float a = (float)values[p];
+    float b[VEC];
+    Pack<T, VEC>::load(Bcol + (size_t)column_indices[p] * n, b);
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = __builtin_fmaf(a, b[v], acc[v]);
+  }
+  if (active) Pack<T, VEC>::store(C + (size_t)row * n + col, acc);
+}
+
+}  // namespace spdl

@@ -1,0 +1,113 @@
+"""CPU-side checks of libspdl: the library loads, exports every declared symbol, validates
+arguments before touching the GPU, and its host routines agree with the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def spdl():
+    import paper_2006_10901_amd as s
+    s.lib()
+    return s
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "spdl.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spdl_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(spdl):
+    names = declared_symbols()
+    assert "spdl_spmm" in names and "spdl_sddmm" in names and len(names) >= 10
+    lib = ctypes.CDLL(spdl.LIB_PATH)
+    for name in names:
+        assert hasattr(lib, name), name
+    assert set(names) == set(spdl.EXPORTS)
+
+
+def test_binding_names_match_the_abi(spdl):
+    for name in declared_symbols():
+        assert callable(getattr(spdl, name)), name
+
+
+def test_invalid_arguments_are_rejected_without_a_gpu(spdl):
+    lib = spdl.lib()
+    null = ctypes.c_void_p(0)
+    one = ctypes.c_void_p(256)     # never dereferenced: the checks fail first
+    assert lib.spdl_spmm(-1, 4, 4, 0, one, one, one, null, one, one, null) == -1
+    assert lib.spdl_spmm(4, 4, 4, 3, null, one, one, null, one, one, null) == -1
+    assert lib.spdl_spmm(4, 4, 4, 3, one, null, one, null, one, one, null) == -1
+    assert lib.spdl_spmm(1 << 20, 4, 1 << 12, 3, one, one, one, null, one, one, null) == -1   # m*n overflow
+    assert lib.spdl_sddmm(4, 4, 4, -3, one, one, one, one, one, null) == -1
+    assert lib.spdl_sddmm(4, 4, 4, 3, one, one, null, one, one, null) == -1
+    assert lib.spdl_spmm_f16(4, -4, 4, 3, one, one, one, null, one, one, null) == -1
+    assert lib.spdl_sddmm_f16(4, 4, 4, 3, one, one, one, one, null, null) == -1
+    # degenerate sizes succeed without launching anything
+    assert lib.spdl_spmm(0, 4, 4, 0, null, null, null, null, null, null, null) == 0
+    assert lib.spdl_spmm(4, 4, 0, 0, one, null, null, null, null, null, null) == 0
+    assert lib.spdl_sddmm(4, 4, 4, 0, one, null, one, one, null, null) == 0
+    assert spdl.spdl_status_string(-1) == "invalid argument"
+    assert spdl.spdl_status_string(0) == "ok"
+    assert spdl.spdl_version() >= 100
+
+
+def test_row_order_matches_oracle(spdl, oracle_lib):
+    for A in (wl.lognormal_rows_csr(500, 256, 0.1, 7), wl.adversarial_csr(77, 90, 8),
+              wl.uniform_mask_csr(64, 64, 0.1, 9)):
+        got = spdl.spdl_build_row_order(A.m, A.row_offsets)
+        assert got.dtype == np.int32
+        assert np.array_equal(got, oracle_lib.row_order(A.m, A.row_offsets))
+    assert spdl.spdl_build_row_order(0, np.zeros(1, np.int32)).shape == (0,)
+
+
+def test_validate_csr_host(spdl):
+    A = wl.adversarial_csr(40, 50, 12)
+    assert spdl.spdl_validate_csr_host(A.m, A.k, A.nnz, A.row_offsets, A.column_indices) == (0, True)
+    U = wl.adversarial_csr(40, 50, 12, sorted_cols=False)
+    assert spdl.spdl_validate_csr_host(U.m, U.k, U.nnz, U.row_offsets, U.column_indices) == (0, False)
+    bad = A.column_indices.copy()
+    bad[3] = A.k
+    assert spdl.spdl_validate_csr_host(A.m, A.k, A.nnz, A.row_offsets, bad)[0] == -3
+    ro = A.row_offsets.copy()
+    ro[5], ro[6] = ro[6] + 1, ro[5]
+    assert spdl.spdl_validate_csr_host(A.m, A.k, A.nnz, ro, A.column_indices)[0] == -3
+    ro = A.row_offsets.copy()
+    ro[0] = 1
+    assert spdl.spdl_validate_csr_host(A.m, A.k, A.nnz, ro, A.column_indices)[0] == -3
+
+
+def test_selection_uses_widest_aligned_vector(spdl):
+    s = spdl.spdl_select_spmm(8192, 10240, 128, 1 << 20, 4, 0, 0)
+    assert s["vec"] == 4 and s["lanes_per_row"] * s["vec"] >= 128
+    assert spdl.spdl_select_spmm(64, 64, 130, 100, 4, 0, 0)["vec"] == 2
+    assert spdl.spdl_select_spmm(64, 64, 63, 100, 4, 0, 0)["vec"] == 1
+    assert spdl.spdl_select_spmm(64, 64, 128, 100, 4, 4, 0)["vec"] == 1      # misaligned base
+    assert spdl.spdl_select_spmm(64, 64, 128, 100, 4, 8, 16)["vec"] == 2
+    assert spdl.spdl_select_spmm(64, 64, 3136, 100, 2, 0, 0)["vec"] == 8
+    d = spdl.spdl_select_sddmm(8192, 10240, 128, 8 << 20, 4, 0, 0)
+    assert d["block_threads"] == 256 and d["grid_x"] * 4 >= 8192
+    assert spdl.spdl_variant_name(0, 0) is not None and spdl.spdl_variant_name(0, 99) is None
+
+
+def test_workload_statistics():
+    A = wl.tiny()["A"]
+    assert A.m == 512 and abs(A.nnz / 512 / 512 - 0.10) < 0.01
+    F = wl.transformer_ffn(1, with_dense=False)["A"]
+    lens = F.row_lengths
+    assert F.m == 4096 and F.k == 1024 and abs(lens.mean() - 102.4) < 2 and lens.std() / lens.mean() < 0.15
+    S = wl.conv1x1(True, with_dense=False)["A"]
+    ls = S.row_lengths
+    assert abs(S.nnz - 104857.6) < 0.011 * 104857.6 and ls.std() / ls.mean() > 0.8
+    for A_ in (A, F, S):
+        for i in range(0, A_.m, 97):
+            c = A_.column_indices[A_.row_offsets[i]:A_.row_offsets[i + 1]]
+            assert np.all(np.diff(c) > 0) and (len(c) == 0 or (c[0] >= 0 and c[-1] < A_.k))
