@@ -117,8 +117,8 @@ def cpu_baseline(lstm90, oracle):
     dt = time.perf_counter() - t0
     return {"value": round(2 * 2.0 * A.nnz * n / dt / 1e9, 2), "unit": "GFLOP/s",
             "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "SpMM + SDDMM of the LSTM problem at 90 % sparsity (nnz=%d, n=128), fp64 "
-                      "accumulation plus the |product| scale, %.2f s" % (A.nnz, dt)}
+            "sample": f"SpMM + SDDMM of the LSTM problem at 90 % sparsity (nnz={A.nnz}, n=128), fp64 "
+                      f"accumulation plus the |product| scale, {dt:.2f} s"}
 
 
 def main():

@@ -43,6 +43,10 @@ def lib():
             raise RuntimeError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2006_10901_amd.build` "
                 "(there is no CPU fallback)")
+        # PyTorch ships its own HIP runtime under the same soname as the system one.  Import
+        # torch first so that libspdl binds to the runtime that owns torch's streams and
+        # allocations; with the opposite order two runtimes would coexist and launches fail.
+        import torch  # noqa: F401
         _lib = ctypes.CDLL(LIB_PATH)
         _lib.spdl_status_string.restype = ctypes.c_char_p
         _lib.spdl_variant_name.restype = ctypes.c_char_p
