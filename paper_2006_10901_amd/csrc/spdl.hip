@@ -11,12 +11,13 @@
 #include "common.hpp"
 #include "sddmm_rowstrip.hpp"
 #include "spmm_rowsplit.hpp"
+#include "spmm_slab.hpp"
 
 namespace {
 
 using namespace spdl;
 
-enum SpmmVariant { kSpmmRowsplit = 0, kSpmmVariants };
+enum SpmmVariant { kSpmmRowsplit = 0, kSpmmSlab = 1, kSpmmVariants };
 enum SddmmVariant { kSddmmRowstrip = 0, kSddmmVariants };
 
 std::atomic<int> g_forced[2] = {{-1}, {-1}};
@@ -45,8 +46,11 @@ inline int pick_group(int n, int vec) {
   return kWave;
 }
 
+constexpr int kSlabS = 256;                       // B rows per LDS slab
+constexpr int kSlabLdsBytes = 2 * (kSlabS + 1) * kSlabTile * 4;
+
 template <typename T>
-void fill_spmm_info(int m, int n, const void* B, const void* C, spdl_launch_info* info) {
+void fill_spmm_rowsplit_info(int m, int n, const void* B, const void* C, spdl_launch_info* info) {
   const int vec = pick_vec<T>(n, B, C, 16 / (int)sizeof(T));
   const int g = pick_group(n, vec);
   info->variant = kSpmmRowsplit;
@@ -56,6 +60,37 @@ void fill_spmm_info(int m, int n, const void* B, const void* C, spdl_launch_info
   info->block_threads = 256;
   info->grid_x = (m + info->rows_per_block - 1) / info->rows_per_block;
   info->grid_y = (n + g * vec - 1) / (g * vec);
+}
+
+template <typename T>
+bool slab_usable(int n, const void* B, const void* C) {
+  return n % 4 == 0 && aligned(B, 4 * sizeof(T)) && aligned(C, 4 * sizeof(T));
+}
+
+void fill_spmm_slab_info(int m, int n, spdl_launch_info* info) {
+  const int panels = (m + kSlabRows - 1) / kSlabRows;
+  const int tiles = (n + kSlabTile - 1) / kSlabTile;
+  info->variant = kSpmmSlab;
+  info->vec = 4;
+  info->lanes_per_row = 16;
+  info->rows_per_block = kSlabRows;
+  info->block_threads = kSlabThreads;
+  info->grid_x = ((panels + 7) / 8) * 8 * tiles;
+  info->grid_y = 1;
+}
+
+// Kernel selection (paper Sec. "Experiments": tile and vector width from the problem shape).
+// The slab kernel re-reads each B row from LDS once per sparse row that uses it, so it pays
+// when a 64-row panel touches the same B row several times: 64 * density >= 2.
+template <typename T>
+void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, spdl_launch_info* info) {
+  int variant = g_forced[0].load();
+  if (variant < 0) {
+    const double reuse = (m > 0 && k > 0) ? 64.0 * (double)nnz / ((double)m * (double)k) : 0.0;
+    variant = (sizeof(T) == 4 && slab_usable<T>(n, B, C) && reuse >= 2.0 && m >= 256) ? kSpmmSlab : kSpmmRowsplit;
+  }
+  if (variant == kSpmmSlab && sizeof(T) == 4 && slab_usable<T>(n, B, C)) fill_spmm_slab_info(m, n, info);
+  else fill_spmm_rowsplit_info<T>(m, n, B, C, info);
 }
 
 template <typename T, int VEC>
@@ -94,9 +129,29 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const 
   if (!ro || !C || (nnz > 0 && (!ci || !val || !B))) return SPDL_ERR_INVALID;
   hipStream_t st = static_cast<hipStream_t>(stream);
   spdl_launch_info li;
-  fill_spmm_info<T>(m, n, B, C, &li);
+  fill_spmm_info<T>(m, k, n, nnz, B, C, &li);
   (void)hipGetLastError();
-  int rc = launch_spmm_rowsplit<T>(li, m, n, ro, ci, val, order, B, C, st);
+  int rc = SPDL_OK;
+  if (li.variant == kSpmmSlab) {
+    if constexpr (sizeof(T) == 4) {
+      static std::atomic<bool> configured{false};
+      auto kernel = spmm_slab_kernel<T, kSlabS>;
+      if (!configured.load()) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSlabLdsBytes) != hipSuccess)
+          return SPDL_ERR_LAUNCH;
+        configured.store(true);
+      }
+      const int panels = (m + kSlabRows - 1) / kSlabRows;
+      const int tiles = (n + kSlabTile - 1) / kSlabTile;
+      kernel<<<dim3(li.grid_x), dim3(kSlabThreads), kSlabLdsBytes, st>>>(m, k, n, tiles, panels, ro, ci, val,
+                                                                        order, B, C);
+    } else {
+      return SPDL_ERR_UNSUPPORTED;
+    }
+  } else {
+    rc = launch_spmm_rowsplit<T>(li, m, n, ro, ci, val, order, B, C, st);
+  }
   if (rc != SPDL_OK) return rc;
   return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
 }
@@ -200,8 +255,8 @@ int spdl_validate_csr_host(int m, int k, int nnz, const int* ro, const int* ci, 
 int spdl_select_spmm(int m, int k, int n, int nnz, int elem_bytes, const void* B, const void* C,
                      spdl_launch_info* info) {
   if (!info || !sizes_ok(m, k, n, nnz) || (elem_bytes != 2 && elem_bytes != 4)) return SPDL_ERR_INVALID;
-  if (elem_bytes == 4) fill_spmm_info<float>(m, n, B, C, info);
-  else fill_spmm_info<_Float16>(m, n, B, C, info);
+  if (elem_bytes == 4) fill_spmm_info<float>(m, k, n, nnz, B, C, info);
+  else fill_spmm_info<_Float16>(m, k, n, nnz, B, C, info);
   return SPDL_OK;
 }
 
@@ -222,7 +277,7 @@ int spdl_force_variant(int op, int variant) {
 }
 
 const char* spdl_variant_name(int op, int variant) {
-  static const char* const spmm[] = {"rowsplit"};
+  static const char* const spmm[] = {"rowsplit", "slab"};
   static const char* const sddmm[] = {"rowstrip"};
   if (op == 0 && variant >= 0 && variant < kSpmmVariants) return spmm[variant];
   if (op == 1 && variant >= 0 && variant < kSddmmVariants) return sddmm[variant];

@@ -219,3 +219,56 @@ def test_config5_conv1x1_fp16(g, oracle_lib, skewed):
     r, _ = spmm_case(g, oracle_lib, A, w["B"], 3136, g.TOL_F16, "sorted", f"conv skewed={skewed} spmm f16")
     r2, _ = sddmm_case(g, oracle_lib, A, w["L"], w["R"], 3136, g.TOL_F16, f"conv skewed={skewed} sddmm f16")
     print(f"conv skewed={skewed}: nnz={A.nnz} max err/S spmm={r:.2e} sddmm={r2:.2e}")
+
+
+# ------------------------------------------------------------------ every kernel family, forced
+@pytest.fixture
+def force():
+    import paper_2006_10901_amd as spdl
+    yield spdl.spdl_force_variant
+    spdl.spdl_force_variant(0, -1)
+    spdl.spdl_force_variant(1, -1)
+
+
+def spmm_variants():
+    import paper_2006_10901_amd as spdl
+    out, v = [], 0
+    while spdl.spdl_variant_name(0, v) is not None:
+        out.append(v)
+        v += 1
+    return out
+
+
+@pytest.mark.parametrize("n", [4, 64, 68, 128, 200, 1028])
+def test_forced_spmm_variants_ragged(g, oracle_lib, force, n):
+    import paper_2006_10901_amd as spdl
+    A = wl.adversarial_csr(203, 700, 900 + n)             # k spans several LDS slabs
+    B = wl.dense(A.k, n, 901 + n)
+    C, S = oracle_lib.spmm(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, B)
+    order = oracle_lib.row_order(A.m, A.row_offsets)
+    results = []
+    for v in spmm_variants():
+        force(0, v)
+        assert spdl.spdl_select_spmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"] == v
+        got = g.gpu_spmm(A, B, n, order)
+        g.assert_close(got, C, S, g.TOL_F32, f"variant {spdl.spdl_variant_name(0, v)} n={n}")
+        results.append(got)
+    # every family adds a row's products in stored order with fused multiply-adds: same bits
+    for r in results[1:]:
+        assert np.array_equal(r, results[0])
+
+
+def test_forced_spmm_variants_unsorted_rows_and_uniform_mask(g, oracle_lib, force):
+    import paper_2006_10901_amd as spdl
+    U = wl.adversarial_csr(150, 600, 77, sorted_cols=False)
+    U.column_indices[5:9] = U.column_indices[5]
+    D = wl.uniform_mask_csr(333, 1000, 0.2, 78)
+    for A in (U, D):
+        n = 128
+        B = wl.dense(A.k, n, 79)
+        C, S = oracle_lib.spmm(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, B)
+        for v in spmm_variants():
+            force(0, v)
+            for order in (None, oracle_lib.row_order(A.m, A.row_offsets)):
+                got = g.gpu_spmm(A, B, n, order)
+                g.assert_close(got, C, S, g.TOL_F32, f"variant {spdl.spdl_variant_name(0, v)}")
