@@ -48,6 +48,7 @@ inline int pick_group(int n, int vec) {
 
 constexpr int kSlabS = 256;                       // B rows per LDS slab
 constexpr int kSlabLdsBytes = 2 * (kSlabS + 1) * kSlabTile * 4;
+constexpr int kComputeUnits = 256;
 
 template <typename T>
 void fill_spmm_rowsplit_info(int m, int n, const void* B, const void* C, spdl_launch_info* info) {
@@ -67,16 +68,28 @@ bool slab_usable(int n, const void* B, const void* C) {
   return n % 4 == 0 && aligned(B, 4 * sizeof(T)) && aligned(C, 4 * sizeof(T));
 }
 
+// One workgroup fits per CU (LDS), so a panel's tiles are split into just enough groups to
+// give every CU a workgroup; each workgroup then walks its tiles back to back.
+int slab_tiles_per_wg(int m, int n) {
+  const int panels = (m + kSlabRows - 1) / kSlabRows;
+  const int tiles = (n + kSlabTile - 1) / kSlabTile;
+  int groups = (kComputeUnits + panels - 1) / panels;
+  groups = std::max(1, std::min(groups, tiles));
+  return (tiles + groups - 1) / groups;
+}
+
 void fill_spmm_slab_info(int m, int n, spdl_launch_info* info) {
   const int panels = (m + kSlabRows - 1) / kSlabRows;
   const int tiles = (n + kSlabTile - 1) / kSlabTile;
+  const int tpw = slab_tiles_per_wg(m, n);
+  const int groups = (tiles + tpw - 1) / tpw;
   info->variant = kSpmmSlab;
   info->vec = 4;
   info->lanes_per_row = 16;
   info->rows_per_block = kSlabRows;
   info->block_threads = kSlabThreads;
-  info->grid_x = ((panels + 7) / 8) * 8 * tiles;
-  info->grid_y = 1;
+  info->grid_x = ((panels + 7) / 8) * 8 * groups;
+  info->grid_y = tpw;                       // tiles walked by one workgroup (the grid is 1-D)
 }
 
 // Kernel selection (paper Sec. "Experiments": tile and vector width from the problem shape).
@@ -144,8 +157,8 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const 
       }
       const int panels = (m + kSlabRows - 1) / kSlabRows;
       const int tiles = (n + kSlabTile - 1) / kSlabTile;
-      kernel<<<dim3(li.grid_x), dim3(kSlabThreads), kSlabLdsBytes, st>>>(m, k, n, tiles, panels, ro, ci, val,
-                                                                        order, B, C);
+      kernel<<<dim3(li.grid_x), dim3(kSlabThreads), kSlabLdsBytes, st>>>(m, k, n, nnz, tiles, li.grid_y, panels, ro,
+                                                                        ci, val, order, B, C);
     } else {
       return SPDL_ERR_UNSUPPORTED;
     }

@@ -1,26 +1,34 @@
-// SpMM, slab family: a workgroup of 16 waves owns 64 sparse rows and a 64-column tile of C.
-// B is streamed through LDS in slabs of S consecutive rows (double buffered), so every B
-// element is fetched from global memory once per workgroup and then re-read from LDS by each
-// sparse row that has a nonzero in that column: reuse of B across rows, which the paper names
-// as the way past its shared-memory bandwidth limit (Sec. "Discussion & Conclusion").
+// SpMM, slab family: a workgroup owns 64 sparse rows (one panel) and walks over one or more
+// 64-column tiles of C.  B is streamed through LDS in slabs of S consecutive rows, so every
+// B element is fetched from global memory once per workgroup and then re-read from LDS by
+// each sparse row that has a nonzero in that column: reuse of B across rows, which the paper
+// names as the way past its shared-memory bandwidth limit (Sec. "Discussion & Conclusion").
 //
-// Inside a wave each 16-lane group owns one sparse row (paper Sec. "Subwarp Tiling": four
-// rows per wave, bundled by length through the row order).  A group fetches 16 consecutive
-// (value, column) pairs of its row with one load each, and the pairs are handed to the
-// group's lanes one at a time by DPP row broadcasts inside the multiply-add itself.  The
-// column index is pre-scaled to an LDS byte offset once per pair (Sec. "Index Pre-Scaling").
+// The 16 waves are specialised.  Waves 8..15 are producers: they only move B slabs from
+// global memory into the LDS buffer that is not being read (two buffers).  Waves 0..7 are
+// consumers.  Vector-memory loads retire in order, so a wave that had both a slab prefetch
+// and its sparse-row loads in flight would stall on the slab every time it needed the next
+// sparse elements; with the split, consumers wait only for their own short loads.
 //
-// Requires ascending column indices inside a row for the slab walk; a row that is not in
-// ascending order is noticed (its cursor does not reach the row end) and redone by direct
-// gathers, so results are always right.  Needs n % 4 == 0 and 16-byte aligned B and C.
+// Inside a consumer wave each 16-lane group owns two sparse rows (paper Sec. "Subwarp
+// Tiling"; rows bundled by length through the row order).  A group fetches 16 consecutive
+// (value, column) pairs of its row with one load each, one round ahead, and the pairs are
+// handed to the group's lanes one at a time by DPP row broadcasts inside the multiply-add.
+// The column index is pre-scaled to an LDS byte offset once per pair (Sec. "Index
+// Pre-Scaling").  Every row's products are added in stored order with fused multiply-adds.
+//
+// The slab walk needs ascending column indices inside a row; a row that is not ascending is
+// noticed (its cursor does not reach the row end) and redone by direct gathers, so results
+// are always right.  Needs n % 4 == 0 and 16-byte aligned B and C.
 #pragma once
 #include "common.hpp"
 
 namespace spdl {
 
-constexpr int kSlabTile = 64;        // output columns per workgroup
-constexpr int kSlabRows = 64;        // sparse rows per workgroup
+constexpr int kSlabTile = 64;          // output columns per tile
+constexpr int kSlabRows = 64;          // sparse rows per workgroup
 constexpr int kSlabThreads = 1024;
+constexpr int kSlabConsumers = 512;    // threads of the consumer waves
 
 // Four consecutive pairs of every 16-lane group: four LDS addresses and 128-bit LDS reads,
 // then sixteen multiply-adds whose first operand is lane T of the group (DPP row_newbcast).
@@ -32,153 +40,226 @@ constexpr int kSlabThreads = 1024;
                "v_fmac_f32_dpp %1, %4, %6 row_newbcast:" #T " row_mask:0xf bank_mask:0xf\n\t"  \
                "v_fmac_f32_dpp %2, %4, %7 row_newbcast:" #T " row_mask:0xf bank_mask:0xf\n\t"  \
                "v_fmac_f32_dpp %3, %4, %8 row_newbcast:" #T " row_mask:0xf bank_mask:0xf"       \
-               : "+v"(acc0), "+v"(acc1), "+v"(acc2), "+v"(acc3)                                \
+               : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])                        \
                : "v"(av), "v"(BV.x), "v"(BV.y), "v"(BV.z), "v"(BV.w));
 
 #define SPDL_DPP_ADDR(T) (__builtin_amdgcn_update_dpp(0, off, 0x150 + (T), 0xf, 0xf, false) + lane_b)
 
-#define SPDL_DPP_GROUP(T0, T1, T2, T3, PRE)                                                    \
-  {                                                                                            \
-    const f32x4 b0 = *reinterpret_cast<const f32x4*>(buf + SPDL_DPP_ADDR(T0));                 \
-    const f32x4 b1 = *reinterpret_cast<const f32x4*>(buf + SPDL_DPP_ADDR(T1));                 \
-    const f32x4 b2 = *reinterpret_cast<const f32x4*>(buf + SPDL_DPP_ADDR(T2));                 \
-    const f32x4 b3 = *reinterpret_cast<const f32x4*>(buf + SPDL_DPP_ADDR(T3));                 \
-    SPDL_DPP_FMA4(T0, b0, PRE)                                                                 \
-    SPDL_DPP_FMA4(T1, b1, "")                                                                  \
-    SPDL_DPP_FMA4(T2, b2, "")                                                                  \
-    SPDL_DPP_FMA4(T3, b3, "")                                                                  \
+// Loads of one group of four pairs into BQ[0..3], and its sixteen multiply-adds.
+#define SPDL_DPP_LOAD4(BQ, T0, T1, T2, T3)                                                     \
+  BQ[0] = *reinterpret_cast<const f32x4*>(buf + SPDL_DPP_ADDR(T0));                            \
+  BQ[1] = *reinterpret_cast<const f32x4*>(buf + SPDL_DPP_ADDR(T1));                            \
+  BQ[2] = *reinterpret_cast<const f32x4*>(buf + SPDL_DPP_ADDR(T2));                            \
+  BQ[3] = *reinterpret_cast<const f32x4*>(buf + SPDL_DPP_ADDR(T3));
+
+#define SPDL_DPP_FMA16(BQ, T0, T1, T2, T3, PRE)                                                \
+  SPDL_DPP_FMA4(T0, BQ[0], PRE)                                                                \
+  SPDL_DPP_FMA4(T1, BQ[1], "")                                                                 \
+  SPDL_DPP_FMA4(T2, BQ[2], "")                                                                 \
+  SPDL_DPP_FMA4(T3, BQ[3], "")
+
+// State of one sparse row inside a 16-lane group.
+struct SlabRow {
+  int row, p_begin, p, row_end;
+  int c_next;
+  float a_next;
+};
+
+// The loads are unconditional (index clamped into the arrays, result discarded past the row
+// end): a load under a branch would make the compiler wait for it at once, and the point of
+// fetching a round ahead is to leave it in flight.
+template <typename T>
+__device__ __forceinline__ void slab_fetch(SlabRow& r, int l16, int last_nz, const int* __restrict__ ci,
+                                           const T* __restrict__ val) {
+  const int idx = r.p + l16;
+  const int safe = min(idx, last_nz);
+  const int c = ci[safe];
+  const float a = (float)val[safe];
+  const bool in = idx < r.row_end;
+  r.c_next = in ? c : 0x7fffffff;
+  r.a_next = in ? a : 0.f;
+}
+
+// All of one row's pairs that fall into the slab [slab_start, slab_start + S).
+template <typename T, int S>
+__device__ __forceinline__ void slab_consume(SlabRow& r, float (&acc)[4], const char* buf,
+                                             int slab_start, int sub, int l16, int lane_b, int last_nz,
+                                             const int* __restrict__ ci, const T* __restrict__ val) {
+  constexpr int kZeroOff = S * kSlabTile * 4;
+  while (true) {
+    const unsigned rel = (unsigned)(r.c_next - slab_start);
+    const bool valid = rel < (unsigned)S;
+    const unsigned long long mask = __ballot(valid);
+    const unsigned piece = (unsigned)(mask >> (sub * 16)) & 0xffffu;
+    const int cnt = __builtin_ctz(~piece | 0x10000u);            // leading pairs inside the slab
+    const int cmax = max(max(__builtin_amdgcn_readlane(cnt, 0), __builtin_amdgcn_readlane(cnt, 16)),
+                         max(__builtin_amdgcn_readlane(cnt, 32), __builtin_amdgcn_readlane(cnt, 48)));
+    if (cmax == 0) break;
+    const bool use = l16 < cnt;
+    const float av = use ? r.a_next : 0.f;
+    const int off = use ? (int)(rel * (kSlabTile * 4)) : kZeroOff;   // LDS byte offset of the B row
+    r.p += cnt;
+    slab_fetch<T>(r, l16, last_nz, ci, val);                        // next round's pairs
+    // LDS reads of the next group of four pairs are issued before the multiply-adds of the
+    // current one, so their latency overlaps arithmetic inside the wave.
+    f32x4 bx[4], by[4];
+    SPDL_DPP_LOAD4(bx, 0, 1, 2, 3)
+    if (cmax > 4) { SPDL_DPP_LOAD4(by, 4, 5, 6, 7) }
+    SPDL_DPP_FMA16(bx, 0, 1, 2, 3, "s_nop 1\n\t")
+    if (cmax > 4) {
+      if (cmax > 8) { SPDL_DPP_LOAD4(bx, 8, 9, 10, 11) }
+      SPDL_DPP_FMA16(by, 4, 5, 6, 7, "")
+      if (cmax > 8) {
+        if (cmax > 12) { SPDL_DPP_LOAD4(by, 12, 13, 14, 15) }
+        SPDL_DPP_FMA16(bx, 8, 9, 10, 11, "")
+        if (cmax > 12) { SPDL_DPP_FMA16(by, 12, 13, 14, 15, "") }
+      }
+    }
+    if (cmax < 16) break;
   }
+}
 
 template <typename T, int S>
 __global__ __launch_bounds__(kSlabThreads) void spmm_slab_kernel(
-    int m, int k, int n, int tiles_n, int panels, const int* __restrict__ row_offsets,
-    const int* __restrict__ column_indices, const T* __restrict__ values,
-    const int* __restrict__ row_order, const T* __restrict__ B, T* __restrict__ C) {
+    int m, int k, int n, int nnz, int tiles_n, int tiles_per_wg, int panels,
+    const int* __restrict__ row_offsets, const int* __restrict__ column_indices,
+    const T* __restrict__ values, const int* __restrict__ row_order, const T* __restrict__ B,
+    T* __restrict__ C) {
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
   constexpr int kBufBytes = (S + 1) * kSlabTile * 4;      // S data rows + one all-zero row
   constexpr int kZeroOff = S * kSlabTile * 4;
-  constexpr int kPasses = S * 16 / kSlabThreads;          // float4 loads per thread per slab
+  constexpr int kPasses = S * 16 / (kSlabThreads - kSlabConsumers);   // float4 loads per producer thread
 
   const int tid = threadIdx.x;
+
+  // Workgroup id -> (panel, tile group): the tile groups of one row panel get ids that are
+  // equal modulo 8, so they run on the same XCD and the panel's part of A stays in one L2.
+  const int groups_n = (tiles_n + tiles_per_wg - 1) / tiles_per_wg;
+  const int per_block = 8 * groups_n;
+  const int blk = blockIdx.x / per_block;
+  const int rem = blockIdx.x - blk * per_block;
+  const int panel = blk * 8 + (rem & 7);
+  if (panel >= panels) return;
+  const int tile_begin = (rem >> 3) * tiles_per_wg;
+  const int tile_end = min(tiles_n, tile_begin + tiles_per_wg);
+  const int nslabs = (k + S - 1) / S;
+  const int stages = (tile_end - tile_begin) * nslabs;
+
+  if (tid < 2 * kSlabTile)
+    *reinterpret_cast<float*>(lds_raw + (tid >> 6) * kBufBytes + kZeroOff + (tid & 63) * 4) = 0.f;
+
+  if (tid >= kSlabConsumers) {
+    // ---------------------------------------------------------------- producer waves
+    const int pt = tid - kSlabConsumers;
+    const int srow = pt >> 4;                 // 0..31
+    const int scol = (pt & 15) * 4;
+    // Two register sets: the loads of stage q+2 are issued before stage q+1 is written to
+    // LDS, so two slabs are in flight per workgroup.  Every load is unconditional (row and
+    // column clamped into B, stage index clamped to the last one): the wait before a store
+    // can then leave exactly the younger set outstanding.  Slab rows past k and tile columns
+    // past n hold clamped copies that no valid column index or stored output ever touches.
+    float stage[2][kPasses][4];
+    const int last_stage = stages - 1;
+    auto gload = [&](int q, float (&st)[kPasses][4]) {
+      q = min(q, last_stage);
+      const int tile = tile_begin + q / nslabs;
+      const int slab = q - (q / nslabs) * nslabs;
+      const int colg = tile * kSlabTile + scol;
+      const T* src = B + (colg < n ? colg : 0);
+#pragma unroll
+      for (int j = 0; j < kPasses; ++j) {
+        const int r = min(slab * S + j * 32 + srow, k - 1);
+        Pack<T, 4>::load(src + (size_t)r * n, st[j]);
+      }
+    };
+    auto lstore = [&](int q, const float (&st)[kPasses][4]) {
+      char* dst = lds_raw + (q & 1) * kBufBytes;
+#pragma unroll
+      for (int j = 0; j < kPasses; ++j) {
+        f32x4 v = {st[j][0], st[j][1], st[j][2], st[j][3]};
+        *reinterpret_cast<f32x4*>(dst + ((j * 32 + srow) * kSlabTile + scol) * 4) = v;
+      }
+    };
+    gload(0, stage[0]);
+    gload(1, stage[1]);
+    lstore(0, stage[0]);
+    __syncthreads();
+    // at the top of iteration q: stage q is in LDS, stage q+1 is in flight to set 1
+    for (int q = 0; q < stages; q += 2) {
+      gload(q + 2, stage[0]);
+      if (q + 1 < stages) lstore(q + 1, stage[1]);
+      __syncthreads();
+      gload(q + 3, stage[1]);
+      if (q + 1 < stages) {
+        if (q + 2 < stages) lstore(q + 2, stage[0]);
+        __syncthreads();
+      }
+    }
+    return;
+  }
+
+  // ------------------------------------------------------------------ consumer waves
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int sub = lane >> 4;
   const int l16 = lane & 15;
   const int lane_b = l16 * 16;
 
-  // Workgroup id -> (panel, tile): the tiles of one row panel get ids that are equal modulo 8,
-  // so they run on the same XCD and the panel's part of A is fetched into one L2 only.
-  const int per_group = 8 * tiles_n;
-  const int grp = blockIdx.x / per_group;
-  const int rem = blockIdx.x - grp * per_group;
-  const int tile = rem >> 3;
-  const int panel = grp * 8 + (rem & 7);
-  if (panel >= panels) return;
-
-  const int slot = panel * kSlabRows + wave * 4 + sub;
-  int row = -1, p = 0, row_end = 0;
-  if (slot < m) {
-    row = row_order ? row_order[slot] : slot;
-    p = row_offsets[row];
-    row_end = row_offsets[row + 1];
+  SlabRow rows[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int slot = panel * kSlabRows + (wave * 4 + sub) * 2 + j;
+    rows[j].row = -1;
+    rows[j].p_begin = rows[j].row_end = 0;
+    if (slot < m) {
+      const int row = row_order ? row_order[slot] : slot;
+      rows[j].row = row;
+      rows[j].p_begin = row_offsets[row];
+      rows[j].row_end = row_offsets[row + 1];
+    }
   }
-  const int p_begin = p;
-  const int col = tile * kSlabTile + l16 * 4;
-  const bool col_ok = col < n;
+  float acc[2][4];
 
-  // staging of B: thread -> (row within pass, 4 columns)
-  const int srow = tid >> 4;
-  const bool scol_ok = (tile * kSlabTile + (tid & 15) * 4) < n;
-  const T* Bst = B + (size_t)(tile * kSlabTile + (scol_ok ? (tid & 15) * 4 : 0));
-  float stage[kPasses][4];
-  auto gload = [&](int slab) {
-#pragma unroll
-    for (int j = 0; j < kPasses; ++j) {
-      const int r = slab * S + j * 64 + srow;
-      if (r < k && scol_ok) {
-        Pack<T, 4>::load(Bst + (size_t)r * n, stage[j]);
-      } else {
-        stage[j][0] = stage[j][1] = stage[j][2] = stage[j][3] = 0.f;
-      }
-    }
-  };
-  auto lstore = [&](int bufi) {
-#pragma unroll
-    for (int j = 0; j < kPasses; ++j) {
-      f32x4 v = {stage[j][0], stage[j][1], stage[j][2], stage[j][3]};
-      *reinterpret_cast<f32x4*>(lds_raw + bufi * kBufBytes + ((j * 64 + srow) * kSlabTile + (tid & 15) * 4) * 4) = v;
-    }
-  };
-  if (tid < 2 * kSlabTile)
-    *reinterpret_cast<float*>(lds_raw + (tid >> 6) * kBufBytes + kZeroOff + (tid & 63) * 4) = 0.f;
-
-  float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
-  const int nslabs = (k + S - 1) / S;
-  gload(0);
-  lstore(0);
   __syncthreads();
-
-  for (int s = 0; s < nslabs; ++s) {
-    if (s + 1 < nslabs) gload(s + 1);
-    const int slab_start = s * S;
-    const char* buf = lds_raw + (s & 1) * kBufBytes;
-    while (true) {
-      const int idx = p + l16;
-      const bool inrow = idx < row_end;
-      int c = 0x7fffffff;
-      float a = 0.f;
-      if (inrow) {
-        c = column_indices[idx];
-        a = (float)values[idx];
-      }
-      const unsigned rel = (unsigned)(c - slab_start);
-      const bool valid = rel < (unsigned)S;
-      const unsigned long long mask = __ballot(valid);
-      const unsigned piece = (unsigned)(mask >> (sub * 16)) & 0xffffu;
-      const int cnt = __builtin_ctz(~piece | 0x10000u);          // leading pairs inside the slab
-      const int cmax = max(max(__builtin_amdgcn_readlane(cnt, 0), __builtin_amdgcn_readlane(cnt, 16)),
-                           max(__builtin_amdgcn_readlane(cnt, 32), __builtin_amdgcn_readlane(cnt, 48)));
-      if (cmax == 0) break;
-      const bool use = l16 < cnt;
-      const float av = use ? a : 0.f;
-      const int off = use ? (int)(rel * (kSlabTile * 4)) : kZeroOff;   // LDS byte offset of the B row
-      SPDL_DPP_GROUP(0, 1, 2, 3, "s_nop 1\n\t")
-      if (cmax > 4) {
-        SPDL_DPP_GROUP(4, 5, 6, 7, "")
-        if (cmax > 8) {
-          SPDL_DPP_GROUP(8, 9, 10, 11, "")
-          if (cmax > 12) SPDL_DPP_GROUP(12, 13, 14, 15, "")
+  int q = 0;
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const int col = tile * kSlabTile + l16 * 4;
+    const bool col_ok = col < n;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      rows[j].p = rows[j].p_begin;
+      acc[j][0] = acc[j][1] = acc[j][2] = acc[j][3] = 0.f;
+      slab_fetch<T>(rows[j], l16, nnz - 1, column_indices, values);
+    }
+    for (int s = 0; s < nslabs; ++s, ++q) {
+      const char* buf = lds_raw + (q & 1) * kBufBytes;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        slab_consume<T, S>(rows[j], acc[j], buf, s * S, sub, l16, lane_b, nnz - 1, column_indices, values);
+      __syncthreads();
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      // A row whose column indices are not ascending leaves its cursor short of the row end:
+      // redo that row from scratch with direct gathers.
+      if (rows[j].p != rows[j].row_end) {
+        acc[j][0] = acc[j][1] = acc[j][2] = acc[j][3] = 0.f;
+        const T* Bcol = B + (col_ok ? col : 0);
+        for (int t = rows[j].p_begin; t < rows[j].row_end; ++t) {
+          const float a = (float)values[t];
+          float b[4];
+          Pack<T, 4>::load(Bcol + (size_t)column_indices[t] * n, b);
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc[j][v] = __builtin_fmaf(a, b[v], acc[j][v]);
         }
       }
-      p += cnt;
-      if (cmax < 16) break;
+      if (rows[j].row >= 0 && col_ok) Pack<T, 4>::store(C + (size_t)rows[j].row * n + col, acc[j]);
     }
-    if (s + 1 < nslabs) lstore((s + 1) & 1);
-    __syncthreads();
-  }
-
-  // A row whose column indices are not ascending leaves its cursor short of the row end:
-  // redo that row from scratch with direct gathers.
-  if (p != row_end) {
-    acc0 = acc1 = acc2 = acc3 = 0.f;
-    const T* Bcol = B + (col_ok ? col : 0);
-    for (int q = p_begin; q < row_end; ++q) {
-      const float a = (float)values[q];
-      float b[4];
-      Pack<T, 4>::load(Bcol + (size_t)column_indices[q] * n, b);
-      acc0 = __builtin_fmaf(a, b[0], acc0);
-      acc1 = __builtin_fmaf(a, b[1], acc1);
-      acc2 = __builtin_fmaf(a, b[2], acc2);
-      acc3 = __builtin_fmaf(a, b[3], acc3);
-    }
-  }
-  if (row >= 0 && col_ok) {
-    const float out[4] = {acc0, acc1, acc2, acc3};
-    Pack<T, 4>::store(C + (size_t)row * n + col, out);
   }
 }
 
-#undef SPDL_DPP_GROUP
+#undef SPDL_DPP_FMA16
+#undef SPDL_DPP_LOAD4
 #undef SPDL_DPP_ADDR
 #undef SPDL_DPP_FMA4
 
