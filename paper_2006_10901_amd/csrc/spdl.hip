@@ -9,6 +9,7 @@
 
 #include "../../include/spdl.h"
 #include "common.hpp"
+#include "sddmm_group.hpp"
 #include "sddmm_rowstrip.hpp"
 #include "spmm_rowsplit.hpp"
 #include "spmm_slab.hpp"
@@ -18,7 +19,7 @@ namespace {
 using namespace spdl;
 
 enum SpmmVariant { kSpmmRowsplit = 0, kSpmmSlab = 1, kSpmmVariants };
-enum SddmmVariant { kSddmmRowstrip = 0, kSddmmVariants };
+enum SddmmVariant { kSddmmRowstrip = 0, kSddmmGroup = 1, kSddmmVariants };
 
 std::atomic<int> g_forced[2] = {{-1}, {-1}};
 
@@ -170,19 +171,34 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const 
 }
 
 template <typename T>
+bool sddmm_group_usable(int n, const void* L, const void* R) {
+  return n > 0 && n % 4 == 0 && aligned(L, 4 * sizeof(T)) && aligned(R, 4 * sizeof(T));
+}
+
+template <typename T>
 void fill_sddmm_info(int m, int n, int nnz, const void* L, const void* R, spdl_launch_info* info) {
-  int vec = pick_vec<T>(n, L, R, 16 / (int)sizeof(T));
-  while (vec > 1 && kWave * vec / 2 >= n) vec /= 2;     // do not idle lanes on short dot products
+  int variant = g_forced[1].load();
+  if (variant < 0) variant = sddmm_group_usable<T>(n, L, R) ? kSddmmGroup : kSddmmRowstrip;
+  if (variant == kSddmmGroup && !sddmm_group_usable<T>(n, L, R)) variant = kSddmmRowstrip;
   const int avg = m > 0 ? nnz / m : 0;
-  const int split = std::max(1, std::min(8, avg / (4 * kStrip)));
-  info->variant = kSddmmRowstrip;
-  info->vec = vec;
-  info->lanes_per_row = kWave;
-  info->rows_per_block = split;             // waves sharing one sparse row
+  info->variant = variant;
   info->block_threads = 256;
+  info->grid_y = 1;
+  int split;
+  if (variant == kSddmmGroup) {
+    split = std::max(1, std::min(16, avg / 128));          // waves sharing one sparse row
+    info->vec = 4;
+    info->lanes_per_row = 16;
+  } else {
+    int vec = pick_vec<T>(n, L, R, 16 / (int)sizeof(T));
+    while (vec > 1 && kWave * vec / 2 >= n) vec /= 2;     // do not idle lanes on short dot products
+    split = std::max(1, std::min(8, avg / (4 * kStrip)));
+    info->vec = vec;
+    info->lanes_per_row = kWave;
+  }
+  info->rows_per_block = split;
   const int64_t waves = (int64_t)m * split;
   info->grid_x = (int)((waves + 3) / 4);
-  info->grid_y = 1;
 }
 
 template <typename T>
@@ -197,6 +213,10 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
   dim3 grid(li.grid_x), block(256);
   const int split = li.rows_per_block;
   (void)hipGetLastError();
+  if (li.variant == kSddmmGroup) {
+    sddmm_group_kernel<T><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out);
+    return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
+  }
   switch (li.vec) {
     case 1: sddmm_rowstrip_kernel<T, 1><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out); break;
     case 2: sddmm_rowstrip_kernel<T, 2><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out); break;
@@ -291,7 +311,7 @@ int spdl_force_variant(int op, int variant) {
 
 const char* spdl_variant_name(int op, int variant) {
   static const char* const spmm[] = {"rowsplit", "slab"};
-  static const char* const sddmm[] = {"rowstrip"};
+  static const char* const sddmm[] = {"rowstrip", "group"};
   if (op == 0 && variant >= 0 && variant < kSpmmVariants) return spmm[variant];
   if (op == 1 && variant >= 0 && variant < kSddmmVariants) return sddmm[variant];
   return nullptr;

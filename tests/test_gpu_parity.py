@@ -272,3 +272,38 @@ def test_forced_spmm_variants_unsorted_rows_and_uniform_mask(g, oracle_lib, forc
             for order in (None, oracle_lib.row_order(A.m, A.row_offsets)):
                 got = g.gpu_spmm(A, B, n, order)
                 g.assert_close(got, C, S, g.TOL_F32, f"variant {spdl.spdl_variant_name(0, v)}")
+
+
+def sddmm_variants():
+    import paper_2006_10901_amd as spdl
+    out, v = [], 0
+    while spdl.spdl_variant_name(1, v) is not None:
+        out.append(v)
+        v += 1
+    return out
+
+
+@pytest.mark.parametrize("n", [4, 64, 68, 128, 200, 1028])
+def test_forced_sddmm_variants_ragged(g, oracle_lib, force, n):
+    import paper_2006_10901_amd as spdl
+    for A in (wl.adversarial_csr(203, 700, 950 + n), wl.adversarial_csr(90, 300, 951 + n, sorted_cols=False)):
+        L, R = wl.dense(A.m, n, 952 + n), wl.dense(A.k, n, 953 + n)
+        out, S = oracle_lib.sddmm(A.m, A.k, n, A.row_offsets, A.column_indices, L, R)
+        for v in sddmm_variants():
+            force(1, v)
+            assert spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"] == v
+            got = g.gpu_sddmm(A, L, R, n)
+            g.assert_close(got, out, S, g.TOL_F32, f"sddmm variant {spdl.spdl_variant_name(1, v)} n={n}")
+
+
+def test_forced_sddmm_variants_fp16_and_long_rows(g, oracle_lib, force):
+    import paper_2006_10901_amd as spdl
+    A = wl.uniform_mask_csr(300, 2000, 0.3, 960)          # ~600 nonzeros per row: several waves per row
+    n = 136
+    for dt, tol in ((np.float32, g.TOL_F32), (np.float16, g.TOL_F16)):
+        L, R = wl.dense(A.m, n, 961, dt), wl.dense(A.k, n, 962, dt)
+        out, S = oracle_lib.sddmm(A.m, A.k, n, A.row_offsets, A.column_indices, L, R)
+        for v in sddmm_variants():
+            force(1, v)
+            got = g.gpu_sddmm(A, L, R, n)
+            g.assert_close(got, out, S, tol, f"sddmm variant {spdl.spdl_variant_name(1, v)} {dt.__name__}")
