@@ -101,7 +101,11 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
   int variant = g_forced[0].load();
   if (variant < 0) {
     const double reuse = (m > 0 && k > 0) ? 64.0 * (double)nnz / ((double)m * (double)k) : 0.0;
-    variant = (sizeof(T) == 4 && slab_usable<T>(n, B, C) && reuse >= 2.0 && m >= 256) ? kSpmmSlab : kSpmmRowsplit;
+    // one workgroup per CU: below half a machine of 64x64 output tiles the row-splitting
+    // kernel, which spreads over many more waves, is faster
+    const int64_t out_tiles = (int64_t)((m + kSlabRows - 1) / kSlabRows) * ((n + kSlabTile - 1) / kSlabTile);
+    variant = (sizeof(T) == 4 && slab_usable<T>(n, B, C) && reuse >= 2.0 && out_tiles >= kComputeUnits / 2)
+                  ? kSpmmSlab : kSpmmRowsplit;
   }
   if (variant == kSpmmSlab && sizeof(T) == 4 && slab_usable<T>(n, B, C)) fill_spmm_slab_info(m, n, info);
   else fill_spmm_rowsplit_info<T>(m, n, B, C, info);
