@@ -46,6 +46,43 @@ __device__ __forceinline__ float reduce16x16(float (&x)[16], int l16) {
                     0, __builtin_bit_cast(int, send), 0xb1 /* quad_perm [1,0,3,2] */, 0xf, 0xf, false));
 }
 
+// Dot products of one strip of up to 16 consecutive nonzeros [q, q+16) ∩ [q, end) of `row`,
+// rows of L and R gathered straight from global memory.  Called by all 16 lanes of a group.
+template <typename T>
+__device__ __forceinline__ void sddmm_strip_direct(int n, int q, int end, int l16, const T* __restrict__ Lrow,
+                                                   const int* __restrict__ column_indices,
+                                                   const T* __restrict__ R, T* __restrict__ out) {
+  const int cidx = q + l16;
+  const int roff = column_indices[min(cidx, end - 1)] * n;     // past the end: last entry again
+  float partial[16];
+#pragma unroll
+  for (int t = 0; t < 16; ++t) partial[t] = 0.f;
+  for (int col0 = 0; col0 < n; col0 += 64) {
+    const int col = col0 + 4 * l16;
+    const bool ok = col < n;
+    const int colc = ok ? col : 0;
+    float l[4];
+    Pack<T, 4>::load(Lrow + colc, l);
+    if (!ok) l[0] = l[1] = l[2] = l[3] = 0.f;
+    const int lane_off = colc;
+#define SPDL_R4(T0)                                                                             \
+  {                                                                                             \
+    float r[4][4];                                                                              \
+    Pack<T, 4>::load(R + (__builtin_amdgcn_update_dpp(0, roff, 0x150 + (T0), 0xf, 0xf, false) + lane_off), r[0]);     \
+    Pack<T, 4>::load(R + (__builtin_amdgcn_update_dpp(0, roff, 0x150 + (T0) + 1, 0xf, 0xf, false) + lane_off), r[1]); \
+    Pack<T, 4>::load(R + (__builtin_amdgcn_update_dpp(0, roff, 0x150 + (T0) + 2, 0xf, 0xf, false) + lane_off), r[2]); \
+    Pack<T, 4>::load(R + (__builtin_amdgcn_update_dpp(0, roff, 0x150 + (T0) + 3, 0xf, 0xf, false) + lane_off), r[3]); \
+    _Pragma("unroll") for (int u = 0; u < 4; ++u)                                               \
+      _Pragma("unroll") for (int v = 0; v < 4; ++v)                                             \
+        partial[(T0) + u] = __builtin_fmaf(l[v], r[u][v], partial[(T0) + u]);                   \
+  }
+    SPDL_R4(0) SPDL_R4(4) SPDL_R4(8) SPDL_R4(12)
+#undef SPDL_R4
+  }
+  const float total = reduce16x16(partial, l16);
+  if (cidx < end) out[cidx] = (T)total;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void sddmm_group_kernel(
     int m, int n, int split, const int* __restrict__ row_offsets,
@@ -61,40 +98,9 @@ __global__ __launch_bounds__(256) void sddmm_group_kernel(
   const int start = row_offsets[row];
   const int end = row_offsets[row + 1];
   const T* Lrow = L + (size_t)row * n;
-
   // the four groups of a wave take strips part*4+sub, then every split*4-th one
-  for (int q0 = start + part * 64; q0 < end; q0 += split * 64) {
-    const int q = q0 + sub * 16;
-    const int cidx = q + l16;
-    const int roff = column_indices[min(cidx, end - 1)] * n;     // past the end: last entry again
-    float partial[16];
-#pragma unroll
-    for (int t = 0; t < 16; ++t) partial[t] = 0.f;
-    for (int col0 = 0; col0 < n; col0 += 64) {
-      const int col = col0 + 4 * l16;
-      const bool ok = col < n;
-      const int colc = ok ? col : 0;
-      float l[4];
-      Pack<T, 4>::load(Lrow + colc, l);
-      if (!ok) l[0] = l[1] = l[2] = l[3] = 0.f;
-      const int lane_off = colc;
-#define SPDL_R4(T0)                                                                             \
-  {                                                                                             \
-    float r[4][4];                                                                              \
-    Pack<T, 4>::load(R + (__builtin_amdgcn_update_dpp(0, roff, 0x150 + (T0), 0xf, 0xf, false) + lane_off), r[0]);     \
-    Pack<T, 4>::load(R + (__builtin_amdgcn_update_dpp(0, roff, 0x150 + (T0) + 1, 0xf, 0xf, false) + lane_off), r[1]); \
-    Pack<T, 4>::load(R + (__builtin_amdgcn_update_dpp(0, roff, 0x150 + (T0) + 2, 0xf, 0xf, false) + lane_off), r[2]); \
-    Pack<T, 4>::load(R + (__builtin_amdgcn_update_dpp(0, roff, 0x150 + (T0) + 3, 0xf, 0xf, false) + lane_off), r[3]); \
-    _Pragma("unroll") for (int u = 0; u < 4; ++u)                                               \
-      _Pragma("unroll") for (int v = 0; v < 4; ++v)                                             \
-        partial[(T0) + u] = __builtin_fmaf(l[v], r[u][v], partial[(T0) + u]);                   \
-  }
-      SPDL_R4(0) SPDL_R4(4) SPDL_R4(8) SPDL_R4(12)
-#undef SPDL_R4
-    }
-    const float total = reduce16x16(partial, l16);
-    if (cidx < end) out[cidx] = (T)total;
-  }
+  for (int q0 = start + part * 64; q0 < end; q0 += split * 64)
+    sddmm_strip_direct<T>(n, q0 + sub * 16, end, l16, Lrow, column_indices, R, out);
 }
 
 }  // namespace spdl

@@ -11,6 +11,7 @@
 #include "common.hpp"
 #include "sddmm_group.hpp"
 #include "sddmm_rowstrip.hpp"
+#include "sddmm_slab.hpp"
 #include "spmm_rowsplit.hpp"
 #include "spmm_slab.hpp"
 
@@ -19,7 +20,7 @@ namespace {
 using namespace spdl;
 
 enum SpmmVariant { kSpmmRowsplit = 0, kSpmmSlab = 1, kSpmmVariants };
-enum SddmmVariant { kSddmmRowstrip = 0, kSddmmGroup = 1, kSddmmVariants };
+enum SddmmVariant { kSddmmRowstrip = 0, kSddmmGroup = 1, kSddmmSlab = 2, kSddmmVariants };
 
 std::atomic<int> g_forced[2] = {{-1}, {-1}};
 
@@ -179,15 +180,55 @@ bool sddmm_group_usable(int n, const void* L, const void* R) {
   return n > 0 && n % 4 == 0 && aligned(L, 4 * sizeof(T)) && aligned(R, 4 * sizeof(T));
 }
 
+// Shape of the slab kernel's launch: U 64-column chunks per LDS row, S = 256/U rows of R per
+// slab, the columns of A split into `ksplit` runs of `spp` slabs so that every CU gets a
+// workgroup.
+struct SddmmSlabShape { int U, S, deferred, ksplit, spp, panels, lds_bytes; };
+
+// Dot products of up to 128 columns are finished inside a slab (U = 1 or 2 chunks of 64
+// columns per LDS row, 64 KB slabs).  Longer ones stream 64-column chunks of 128-row slabs and
+// keep two strips per row and slab in registers.
+SddmmSlabShape sddmm_slab_shape(int m, int k, int n) {
+  SddmmSlabShape sh;
+  sh.deferred = n > 128;
+  sh.U = (n <= 64 || sh.deferred) ? 1 : 2;
+  sh.S = sh.deferred ? 128 : 256 / sh.U;
+  sh.panels = (m + kSdRows - 1) / kSdRows;
+  const int total = std::max(1, (k + sh.S - 1) / sh.S);
+  const int want = std::max(1, std::min(total, (kComputeUnits + sh.panels - 1) / sh.panels));
+  sh.spp = (total + want - 1) / want;
+  sh.ksplit = (total + sh.spp - 1) / sh.spp;
+  sh.lds_bytes = 2 * (sh.S + 1) * 256 * sh.U;
+  return sh;
+}
+
 template <typename T>
-void fill_sddmm_info(int m, int n, int nnz, const void* L, const void* R, spdl_launch_info* info) {
+void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R, spdl_launch_info* info) {
+  const bool fast_ok = sddmm_group_usable<T>(n, L, R);
   int variant = g_forced[1].load();
-  if (variant < 0) variant = sddmm_group_usable<T>(n, L, R) ? kSddmmGroup : kSddmmRowstrip;
-  if (variant == kSddmmGroup && !sddmm_group_usable<T>(n, L, R)) variant = kSddmmRowstrip;
+  if (variant < 0) {
+    const double reuse = (m > 0 && k > 0) ? 64.0 * (double)nnz / ((double)m * (double)k) : 0.0;
+    // wide dot products keep at most 32 nonzeros per row and 128-column slab in registers
+    const bool fits = n <= 128 || 128.0 * (double)nnz / ((double)m * (double)k) <= 16.0;
+    variant = !fast_ok ? kSddmmRowstrip
+              : (sizeof(T) == 4 && reuse >= 2.0 && m >= 512 && fits) ? kSddmmSlab : kSddmmGroup;
+  }
+  if (variant == kSddmmSlab && !(fast_ok && sizeof(T) == 4)) variant = kSddmmGroup;
+  if (variant == kSddmmGroup && !fast_ok) variant = kSddmmRowstrip;
   const int avg = m > 0 ? nnz / m : 0;
   info->variant = variant;
   info->block_threads = 256;
   info->grid_y = 1;
+  if (variant == kSddmmSlab) {
+    const SddmmSlabShape sh = sddmm_slab_shape(m, k, n);
+    info->vec = 4 * sh.U;
+    info->lanes_per_row = 16;
+    info->rows_per_block = kSdRows;
+    info->block_threads = kSdThreads;
+    info->grid_x = ((sh.panels + 7) / 8) * 8 * sh.ksplit;
+    info->grid_y = sh.ksplit;               // column ranges of A (the grid is 1-D)
+    return;
+  }
   int split;
   if (variant == kSddmmGroup) {
     split = std::max(1, std::min(16, avg / 128));          // waves sharing one sparse row
@@ -205,6 +246,22 @@ void fill_sddmm_info(int m, int n, int nnz, const void* L, const void* R, spdl_l
   info->grid_x = (int)((waves + 3) / 4);
 }
 
+template <typename T, int U, int S, bool DEFERRED>
+int launch_sddmm_slab(const SddmmSlabShape& sh, int grid, int m, int k, int n, int nnz, const int* ro,
+                      const int* ci, const T* L, const T* R, T* out, hipStream_t st) {
+  static std::atomic<bool> configured{false};
+  auto kernel = sddmm_slab_kernel<T, U, S, DEFERRED>;
+  if (!configured.load()) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            sh.lds_bytes) != hipSuccess)
+      return SPDL_ERR_LAUNCH;
+    configured.store(true);
+  }
+  kernel<<<dim3(grid), dim3(kSdThreads), sh.lds_bytes, st>>>(m, k, n, nnz, sh.ksplit, sh.spp, sh.panels, ro, ci,
+                                                             L, R, out);
+  return SPDL_OK;
+}
+
 template <typename T>
 int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const T* L, const T* R,
                T* out, void* stream) {
@@ -213,10 +270,23 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
   if (!ro || !ci || !out || (n > 0 && (!L || !R))) return SPDL_ERR_INVALID;
   hipStream_t st = static_cast<hipStream_t>(stream);
   spdl_launch_info li;
-  fill_sddmm_info<T>(m, n, nnz, L, R, &li);
+  fill_sddmm_info<T>(m, k, n, nnz, L, R, &li);
   dim3 grid(li.grid_x), block(256);
   const int split = li.rows_per_block;
   (void)hipGetLastError();
+  if (li.variant == kSddmmSlab) {
+    if constexpr (sizeof(T) == 4) {
+      const SddmmSlabShape sh = sddmm_slab_shape(m, k, n);
+      int rc;
+      if (sh.deferred) rc = launch_sddmm_slab<T, 1, 128, true>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, st);
+      else if (sh.U == 1) rc = launch_sddmm_slab<T, 1, 256, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, st);
+      else rc = launch_sddmm_slab<T, 2, 128, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, st);
+      if (rc != SPDL_OK) return rc;
+      return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
+    } else {
+      return SPDL_ERR_UNSUPPORTED;
+    }
+  }
   if (li.variant == kSddmmGroup) {
     sddmm_group_kernel<T><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out);
     return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
@@ -300,8 +370,8 @@ int spdl_select_spmm(int m, int k, int n, int nnz, int elem_bytes, const void* B
 int spdl_select_sddmm(int m, int k, int n, int nnz, int elem_bytes, const void* L, const void* R,
                       spdl_launch_info* info) {
   if (!info || !sizes_ok(m, k, n, nnz) || (elem_bytes != 2 && elem_bytes != 4)) return SPDL_ERR_INVALID;
-  if (elem_bytes == 4) fill_sddmm_info<float>(m, n, nnz, L, R, info);
-  else fill_sddmm_info<_Float16>(m, n, nnz, L, R, info);
+  if (elem_bytes == 4) fill_sddmm_info<float>(m, k, n, nnz, L, R, info);
+  else fill_sddmm_info<_Float16>(m, k, n, nnz, L, R, info);
   return SPDL_OK;
 }
 
@@ -315,7 +385,7 @@ int spdl_force_variant(int op, int variant) {
 
 const char* spdl_variant_name(int op, int variant) {
   static const char* const spmm[] = {"rowsplit", "slab"};
-  static const char* const sddmm[] = {"rowstrip", "group"};
+  static const char* const sddmm[] = {"rowstrip", "group", "slab"};
   if (op == 0 && variant >= 0 && variant < kSpmmVariants) return spmm[variant];
   if (op == 1 && variant >= 0 && variant < kSddmmVariants) return sddmm[variant];
   return nullptr;
