@@ -14,12 +14,13 @@
 #include "sddmm_slab.hpp"
 #include "spmm_rowsplit.hpp"
 #include "spmm_slab.hpp"
+#include "spmm_slab_dma.hpp"
 
 namespace {
 
 using namespace spdl;
 
-enum SpmmVariant { kSpmmRowsplit = 0, kSpmmSlab = 1, kSpmmVariants };
+enum SpmmVariant { kSpmmRowsplit = 0, kSpmmSlab = 1, kSpmmSlabDma = 2, kSpmmVariants };
 enum SddmmVariant { kSddmmRowstrip = 0, kSddmmGroup = 1, kSddmmSlab = 2, kSddmmVariants };
 
 std::atomic<int> g_forced[2] = {{-1}, {-1}};
@@ -66,8 +67,8 @@ void fill_spmm_rowsplit_info(int m, int n, const void* B, const void* C, spdl_la
 }
 
 template <typename T>
-bool slab_usable(int n, const void* B, const void* C) {
-  return n % 4 == 0 && aligned(B, 4 * sizeof(T)) && aligned(C, 4 * sizeof(T));
+bool slab_usable(int n, int nnz, const void* B, const void* C) {
+  return n % 4 == 0 && nnz < (1 << 29) && aligned(B, 4 * sizeof(T)) && aligned(C, 4 * sizeof(T));
 }
 
 // One workgroup fits per CU (LDS), so a panel's tiles are split into just enough groups to
@@ -105,11 +106,15 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
     // one workgroup per CU: below half a machine of 64x64 output tiles the row-splitting
     // kernel, which spreads over many more waves, is faster
     const int64_t out_tiles = (int64_t)((m + kSlabRows - 1) / kSlabRows) * ((n + kSlabTile - 1) / kSlabTile);
-    variant = (sizeof(T) == 4 && slab_usable<T>(n, B, C) && reuse >= 2.0 && out_tiles >= kComputeUnits / 2)
-                  ? kSpmmSlab : kSpmmRowsplit;
+    variant = (sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) && reuse >= 2.0 && out_tiles >= kComputeUnits / 2)
+                  ? kSpmmSlabDma : kSpmmRowsplit;
   }
-  if (variant == kSpmmSlab && sizeof(T) == 4 && slab_usable<T>(n, B, C)) fill_spmm_slab_info(m, n, info);
-  else fill_spmm_rowsplit_info<T>(m, n, B, C, info);
+  if ((variant == kSpmmSlab || variant == kSpmmSlabDma) && sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C)) {
+    fill_spmm_slab_info(m, n, info);
+    info->variant = variant;
+  } else {
+    fill_spmm_rowsplit_info<T>(m, n, B, C, info);
+  }
 }
 
 template <typename T, int VEC>
@@ -151,20 +156,27 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const 
   fill_spmm_info<T>(m, k, n, nnz, B, C, &li);
   (void)hipGetLastError();
   int rc = SPDL_OK;
-  if (li.variant == kSpmmSlab) {
+  if (li.variant == kSpmmSlab || li.variant == kSpmmSlabDma) {
     if constexpr (sizeof(T) == 4) {
       static std::atomic<bool> configured{false};
       auto kernel = spmm_slab_kernel<T, kSlabS>;
+      auto kernel_dma = spmm_slab_dma_kernel<kSlabS>;
       if (!configured.load()) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSlabLdsBytes) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(kernel_dma),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSlabLdsBytes) != hipSuccess)
           return SPDL_ERR_LAUNCH;
         configured.store(true);
       }
       const int panels = (m + kSlabRows - 1) / kSlabRows;
       const int tiles = (n + kSlabTile - 1) / kSlabTile;
-      kernel<<<dim3(li.grid_x), dim3(kSlabThreads), kSlabLdsBytes, st>>>(m, k, n, nnz, tiles, li.grid_y, panels, ro,
-                                                                        ci, val, order, B, C);
+      if (li.variant == kSpmmSlab)
+        kernel<<<dim3(li.grid_x), dim3(kSlabThreads), kSlabLdsBytes, st>>>(m, k, n, nnz, tiles, li.grid_y, panels,
+                                                                          ro, ci, val, order, B, C);
+      else
+        kernel_dma<<<dim3(li.grid_x), dim3(kSlabThreads), kSlabLdsBytes, st>>>(m, k, n, nnz, tiles, li.grid_y,
+                                                                              panels, ro, ci, val, order, B, C);
     } else {
       return SPDL_ERR_UNSUPPORTED;
     }
@@ -384,7 +396,7 @@ int spdl_force_variant(int op, int variant) {
 }
 
 const char* spdl_variant_name(int op, int variant) {
-  static const char* const spmm[] = {"rowsplit", "slab"};
+  static const char* const spmm[] = {"rowsplit", "slab", "slabdma"};
   static const char* const sddmm[] = {"rowstrip", "group", "slab"};
   if (op == 0 && variant >= 0 && variant < kSpmmVariants) return spmm[variant];
   if (op == 1 && variant >= 0 && variant < kSddmmVariants) return sddmm[variant];

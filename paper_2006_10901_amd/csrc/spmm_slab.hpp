@@ -67,18 +67,22 @@ struct SlabRow {
 
 // The loads are unconditional (index clamped into the arrays, result discarded past the row
 // end): a load under a branch would make the compiler wait for it at once, and the point of
-// fetching a round ahead is to leave it in flight.
+// fetching a round ahead is to leave it in flight.  Byte offsets are 32-bit so that the loads
+// use a scalar base plus a vector offset (nnz < 2^29 is checked on the host).
 template <typename T>
 __device__ __forceinline__ void slab_fetch(SlabRow& r, int l16, int last_nz, const int* __restrict__ ci,
                                            const T* __restrict__ val) {
   const int idx = r.p + l16;
-  const int safe = min(idx, last_nz);
-  const int c = ci[safe];
-  const float a = (float)val[safe];
+  const unsigned safe = (unsigned)min(idx, last_nz);
+  const int c = *reinterpret_cast<const int*>(reinterpret_cast<const char*>(ci) + (safe << 2));
+  const float a = (float)*reinterpret_cast<const T*>(reinterpret_cast<const char*>(val) + safe * (unsigned)sizeof(T));
   const bool in = idx < r.row_end;
   r.c_next = in ? c : 0x7fffffff;
   r.a_next = in ? a : 0.f;
 }
+
+// Number of leading set bits of a 16-bit piece of a wave mask (scalar arithmetic).
+__device__ __forceinline__ int leading16(unsigned piece) { return __builtin_ctz(~piece | 0x10000u); }
 
 // All of one row's pairs that fall into the slab [slab_start, slab_start + S).
 template <typename T, int S>
@@ -86,31 +90,42 @@ __device__ __forceinline__ void slab_consume(SlabRow& r, float (&acc)[4], const 
                                              int slab_start, int sub, int l16, int lane_b, int last_nz,
                                              const int* __restrict__ ci, const T* __restrict__ val) {
   constexpr int kZeroOff = S * kSlabTile * 4;
+  const int sub8 = sub * 8;
   while (true) {
     const unsigned rel = (unsigned)(r.c_next - slab_start);
     const bool valid = rel < (unsigned)S;
+    // Everything derived from the wave mask is wave-uniform and stays in scalar registers:
+    // per-group counts of leading pairs inside the slab, their maximum, and the four counts
+    // packed into one word from which each lane extracts its group's.
     const unsigned long long mask = __ballot(valid);
-    const unsigned piece = (unsigned)(mask >> (sub * 16)) & 0xffffu;
-    const int cnt = __builtin_ctz(~piece | 0x10000u);            // leading pairs inside the slab
-    const int cmax = max(max(__builtin_amdgcn_readlane(cnt, 0), __builtin_amdgcn_readlane(cnt, 16)),
-                         max(__builtin_amdgcn_readlane(cnt, 32), __builtin_amdgcn_readlane(cnt, 48)));
+    if (mask == 0) break;
+    const unsigned lo = (unsigned)mask, hi = (unsigned)(mask >> 32);
+    const int c0 = leading16(lo & 0xffffu), c1 = leading16(lo >> 16);
+    const int c2 = leading16(hi & 0xffffu), c3 = leading16(hi >> 16);
+    const int cmax = max(max(c0, c1), max(c2, c3));
     if (cmax == 0) break;
-    const bool use = l16 < cnt;
-    const float av = use ? r.a_next : 0.f;
-    const int off = use ? (int)(rel * (kSlabTile * 4)) : kZeroOff;   // LDS byte offset of the B row
+    const unsigned packed = (unsigned)c0 | ((unsigned)c1 << 8) | ((unsigned)c2 << 16) | ((unsigned)c3 << 24);
+    const int cnt = (int)((packed >> sub8) & 0xffu);
+    // A pair inside the slab is used even if it is not among the leading ones (rows that are
+    // not ascending): the cursor then stops short of the row end and the row is redone.
+    const float av = valid ? r.a_next : 0.f;
+    const int off = valid ? (int)(rel * (kSlabTile * 4)) : kZeroOff;   // LDS byte offset of the B row
     r.p += cnt;
     slab_fetch<T>(r, l16, last_nz, ci, val);                        // next round's pairs
     // LDS reads of the next group of four pairs are issued before the multiply-adds of the
     // current one, so their latency overlaps arithmetic inside the wave.
+    // The reads one group ahead are issued whether or not that group is needed (every offset
+    // is a valid LDS address), so that the wait before each block of multiply-adds can leave
+    // exactly the younger four reads outstanding.
     f32x4 bx[4], by[4];
     SPDL_DPP_LOAD4(bx, 0, 1, 2, 3)
-    if (cmax > 4) { SPDL_DPP_LOAD4(by, 4, 5, 6, 7) }
+    SPDL_DPP_LOAD4(by, 4, 5, 6, 7)
     SPDL_DPP_FMA16(bx, 0, 1, 2, 3, "s_nop 1\n\t")
     if (cmax > 4) {
-      if (cmax > 8) { SPDL_DPP_LOAD4(bx, 8, 9, 10, 11) }
+      SPDL_DPP_LOAD4(bx, 8, 9, 10, 11)
       SPDL_DPP_FMA16(by, 4, 5, 6, 7, "")
       if (cmax > 8) {
-        if (cmax > 12) { SPDL_DPP_LOAD4(by, 12, 13, 14, 15) }
+        SPDL_DPP_LOAD4(by, 12, 13, 14, 15)
         SPDL_DPP_FMA16(bx, 8, 9, 10, 11, "")
         if (cmax > 12) { SPDL_DPP_FMA16(by, 12, 13, 14, 15, "") }
       }

@@ -86,8 +86,10 @@ def test_validate_csr_host(spdl):
 
 
 def test_selection_uses_widest_aligned_vector(spdl):
-    s = spdl.spdl_select_spmm(8192, 10240, 128, 1 << 20, 4, 0, 0)
+    s = spdl.spdl_select_spmm(8192, 10240, 128, 1 << 20, 4, 0, 0)          # 98.75 % sparse: row splitting
     assert s["vec"] == 4 and s["lanes_per_row"] * s["vec"] >= 128
+    s = spdl.spdl_select_spmm(8192, 10240, 128, 8 << 20, 4, 0, 0)          # 90 % sparse: LDS slabs
+    assert spdl.spdl_variant_name(0, s["variant"]) == "slabdma" and s["grid_x"] == 256
     assert spdl.spdl_select_spmm(64, 64, 130, 100, 4, 0, 0)["vec"] == 2
     assert spdl.spdl_select_spmm(64, 64, 63, 100, 4, 0, 0)["vec"] == 1
     assert spdl.spdl_select_spmm(64, 64, 128, 100, 4, 4, 0)["vec"] == 1      # misaligned base
