@@ -28,6 +28,15 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3      # 256 CUs x 2.4 GHz x 256 flop/clk/CU (publ
 HBM_PEAK_GBS = 8000.0
 
 
+# HBM bytes per launch (read + written) of each kernel family on this workload, from the two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarised in profiles/lstm_sweep_hbm_traffic.md,
+# scaled by the copy-kernel factors given there.  Counters cannot be read from inside this
+# process, so the figures are carried here and refreshed whenever the kernels change.
+MEASURED_HBM_TRAFFIC_BYTES = {
+    "spmm_slabdma": 158.6e6, "sddmm_slab": 174.5e6, "spmm_rowsplit": 80.2e6, "sddmm_group": 154.1e6,
+}
+
+
 def spmm_bytes(m, k, n, nnz, eb=4):
     return nnz * (eb + 4) + (m + 1) * 4 + m * 4 + k * n * eb + m * n * eb
 
@@ -133,6 +142,8 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the Transformer/attention/conv report")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--only", default="", help="comma list of LSTM sparsities to run (profiling aid)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain 256 MiB device copies (reference dispatches for rocprofv3 --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU path exists")
@@ -155,6 +166,14 @@ def main():
         cases.append(Case(f"lstm{sp}", "sddmm", w["A"], 128, (w["L"], w["R"]), spdl, torch))
         log(f"[bench] lstm {sp}%: nnz={w['A'].nnz} generated+uploaded in {time.time() - t0:.1f}s")
 
+    if args.copy_calibration:
+        # a plain copy kernel of known size: 256 MiB read + 256 MiB written per dispatch
+        src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
     wall = time_cases(cases, args.steps, args.warmup, torch)
     ms_per_step = wall / args.steps * 1e3
     step_flops = sum(c.flops for c in cases)
@@ -171,7 +190,9 @@ def main():
     achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
     roofline = {
         "bound": "alu", "achieved": round(achieved, 3), "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
-        "frac": round(achieved / FP32_VECTOR_PEAK_TFLOPS, 4), "traffic": None,
+        "frac": round(achieved / FP32_VECTOR_PEAK_TFLOPS, 4),
+        "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(f"{dom_op}_{dom_kernel}"),
+        "algorithmic_bytes_per_launch": dom["bytes"] / dom["launches"],
         "kernel": f"{dom_op}_{dom_kernel}", "avg_launch_us": round(dom["ms"] / dom["launches"] * 1e3, 2),
         "flops_per_launch": dom["flops"] / dom["launches"],
         "eff_GBs": round(dom["bytes"] / (dom["ms"] * 1e-3) / 1e9, 1),
