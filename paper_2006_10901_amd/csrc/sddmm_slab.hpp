@@ -69,28 +69,33 @@ struct SdRow {
   int c_next2;    // ... and of the 16 after them (two-strip mode only)
 };
 
-// Unconditional loads at clamped positions, so that they can stay in flight.
+// Unconditional loads at clamped positions, so that they can stay in flight; 32-bit byte
+// offsets from a scalar base (nnz < 2^29 is checked on the host).
 template <bool TWO>
 __device__ __forceinline__ void sd_fetch(SdRow& r, int l16, int last_nz, const int* __restrict__ ci) {
   const int idx = r.p + l16;
-  const int c = ci[min(idx, last_nz)];
+  const char* base = reinterpret_cast<const char*>(ci);
+  const int c = *reinterpret_cast<const int*>(base + ((unsigned)min(idx, last_nz) << 2));
   r.c_next = idx < r.row_end ? c : 0x7fffffff;
   if (TWO) {
-    const int c2 = ci[min(idx + 16, last_nz)];
+    const int c2 = *reinterpret_cast<const int*>(base + ((unsigned)min(idx + 16, last_nz) << 2));
     r.c_next2 = idx + 16 < r.row_end ? c2 : 0x7fffffff;
   }
 }
 
 // Leading nonzeros of the fetched strip that fall into [slab_start, slab_start + S): count for
 // this group (cnt), maximum over the wave's groups (return value), slab-relative column.
+// Everything derived from the wave mask is wave-uniform and stays in scalar registers.
 template <int S>
 __device__ __forceinline__ int sd_scan(int c, int slab_start, int sub, unsigned& rel, int& cnt) {
   rel = (unsigned)(c - slab_start);
   const unsigned long long mask = __ballot(rel < (unsigned)S);
-  const unsigned piece = (unsigned)(mask >> (sub * 16)) & 0xffffu;
-  cnt = __builtin_ctz(~piece | 0x10000u);
-  return max(max(__builtin_amdgcn_readlane(cnt, 0), __builtin_amdgcn_readlane(cnt, 16)),
-             max(__builtin_amdgcn_readlane(cnt, 32), __builtin_amdgcn_readlane(cnt, 48)));
+  const unsigned lo = (unsigned)mask, hi = (unsigned)(mask >> 32);
+  const int c0 = __builtin_ctz(~(lo & 0xffffu) | 0x10000u), c1 = __builtin_ctz(~(lo >> 16) | 0x10000u);
+  const int c2 = __builtin_ctz(~(hi & 0xffffu) | 0x10000u), c3 = __builtin_ctz(~(hi >> 16) | 0x10000u);
+  const unsigned packed = (unsigned)c0 | ((unsigned)c1 << 8) | ((unsigned)c2 << 16) | ((unsigned)c3 << 24);
+  cnt = (int)((packed >> (sub * 8)) & 0xffu);
+  return max(max(c0, c1), max(c2, c3));
 }
 
 #define SPDL_SD_ADDR(T) (__builtin_amdgcn_update_dpp(0, off, 0x150 + (T), 0xf, 0xf, false) + lane_b)

@@ -12,6 +12,7 @@
 #include "sddmm_group.hpp"
 #include "sddmm_rowstrip.hpp"
 #include "sddmm_slab.hpp"
+#include "sddmm_slab_dma.hpp"
 #include "spmm_rowsplit.hpp"
 #include "spmm_slab.hpp"
 #include "spmm_slab_dma.hpp"
@@ -21,7 +22,7 @@ namespace {
 using namespace spdl;
 
 enum SpmmVariant { kSpmmRowsplit = 0, kSpmmSlab = 1, kSpmmSlabDma = 2, kSpmmVariants };
-enum SddmmVariant { kSddmmRowstrip = 0, kSddmmGroup = 1, kSddmmSlab = 2, kSddmmVariants };
+enum SddmmVariant { kSddmmRowstrip = 0, kSddmmGroup = 1, kSddmmSlab = 2, kSddmmSlabDma = 3, kSddmmVariants };
 
 std::atomic<int> g_forced[2] = {{-1}, {-1}};
 
@@ -223,15 +224,16 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
     // wide dot products keep at most 32 nonzeros per row and 128-column slab in registers
     const bool fits = n <= 128 || 128.0 * (double)nnz / ((double)m * (double)k) <= 16.0;
     variant = !fast_ok ? kSddmmRowstrip
-              : (sizeof(T) == 4 && reuse >= 2.0 && m >= 512 && fits) ? kSddmmSlab : kSddmmGroup;
+              : (sizeof(T) == 4 && reuse >= 2.0 && m >= 512 && fits && nnz < (1 << 29)) ? kSddmmSlabDma : kSddmmGroup;
   }
-  if (variant == kSddmmSlab && !(fast_ok && sizeof(T) == 4)) variant = kSddmmGroup;
+  if ((variant == kSddmmSlab || variant == kSddmmSlabDma) && !(fast_ok && sizeof(T) == 4 && nnz < (1 << 29)))
+    variant = kSddmmGroup;
   if (variant == kSddmmGroup && !fast_ok) variant = kSddmmRowstrip;
   const int avg = m > 0 ? nnz / m : 0;
   info->variant = variant;
   info->block_threads = 256;
   info->grid_y = 1;
-  if (variant == kSddmmSlab) {
+  if (variant == kSddmmSlab || variant == kSddmmSlabDma) {
     const SddmmSlabShape sh = sddmm_slab_shape(m, k, n);
     info->vec = 4 * sh.U;
     info->lanes_per_row = 16;
@@ -260,8 +262,21 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
 
 template <typename T, int U, int S, bool DEFERRED>
 int launch_sddmm_slab(const SddmmSlabShape& sh, int grid, int m, int k, int n, int nnz, const int* ro,
-                      const int* ci, const T* L, const T* R, T* out, hipStream_t st) {
+                      const int* ci, const T* L, const T* R, T* out, hipStream_t st, bool dma) {
   static std::atomic<bool> configured{false};
+  static std::atomic<bool> configured_dma{false};
+  if (dma) {
+    auto kernel = sddmm_slab_dma_kernel<U, S, DEFERRED>;
+    if (!configured_dma.load()) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              sh.lds_bytes) != hipSuccess)
+        return SPDL_ERR_LAUNCH;
+      configured_dma.store(true);
+    }
+    kernel<<<dim3(grid), dim3(kSdThreads), sh.lds_bytes, st>>>(m, k, n, nnz, sh.ksplit, sh.spp, sh.panels, ro, ci,
+                                                               L, R, out);
+    return SPDL_OK;
+  }
   auto kernel = sddmm_slab_kernel<T, U, S, DEFERRED>;
   if (!configured.load()) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -286,13 +301,14 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
   dim3 grid(li.grid_x), block(256);
   const int split = li.rows_per_block;
   (void)hipGetLastError();
-  if (li.variant == kSddmmSlab) {
+  if (li.variant == kSddmmSlab || li.variant == kSddmmSlabDma) {
     if constexpr (sizeof(T) == 4) {
       const SddmmSlabShape sh = sddmm_slab_shape(m, k, n);
+      const bool dma = li.variant == kSddmmSlabDma;
       int rc;
-      if (sh.deferred) rc = launch_sddmm_slab<T, 1, 128, true>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, st);
-      else if (sh.U == 1) rc = launch_sddmm_slab<T, 1, 256, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, st);
-      else rc = launch_sddmm_slab<T, 2, 128, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, st);
+      if (sh.deferred) rc = launch_sddmm_slab<T, 1, 128, true>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, st, dma);
+      else if (sh.U == 1) rc = launch_sddmm_slab<T, 1, 256, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, st, dma);
+      else rc = launch_sddmm_slab<T, 2, 128, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, st, dma);
       if (rc != SPDL_OK) return rc;
       return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
     } else {
@@ -397,7 +413,7 @@ int spdl_force_variant(int op, int variant) {
 
 const char* spdl_variant_name(int op, int variant) {
   static const char* const spmm[] = {"rowsplit", "slab", "slabdma"};
-  static const char* const sddmm[] = {"rowstrip", "group", "slab"};
+  static const char* const sddmm[] = {"rowstrip", "group", "slab", "slabdma"};
   if (op == 0 && variant >= 0 && variant < kSpmmVariants) return spmm[variant];
   if (op == 1 && variant >= 0 && variant < kSddmmVariants) return sddmm[variant];
   return nullptr;
