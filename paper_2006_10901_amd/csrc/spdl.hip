@@ -74,23 +74,30 @@ bool slab_usable(int n, int nnz, const void* B, const void* C) {
 
 // One workgroup fits per CU (LDS), so a panel's tiles are split into just enough groups to
 // give every CU a workgroup; each workgroup then walks its tiles back to back.
-int slab_tiles_per_wg(int m, int n) {
-  const int panels = (m + kSlabRows - 1) / kSlabRows;
-  const int tiles = (n + kSlabTile - 1) / kSlabTile;
+int slab_tiles_per_wg(int panels, int tiles) {
   int groups = (kComputeUnits + panels - 1) / panels;
   groups = std::max(1, std::min(groups, tiles));
   return (tiles + groups - 1) / groups;
 }
 
-void fill_spmm_slab_info(int m, int n, spdl_launch_info* info) {
-  const int panels = (m + kSlabRows - 1) / kSlabRows;
+// Rows per 16-lane group of the copy-based slab kernel: two when 128-row panels still give
+// every CU at least two tiles to walk, else one.
+int slab_rows_per_group(int m, int n) {
+  const int64_t tiles128 = (int64_t)((m + 127) / 128) * ((n + kSlabTile - 1) / kSlabTile);
+  return tiles128 >= 2 * kComputeUnits ? 2 : 1;
+}
+
+void fill_spmm_slab_info(int m, int n, int variant, spdl_launch_info* info) {
+  const int rpg = variant == kSpmmSlabDma ? slab_rows_per_group(m, n) : 1;
+  const int rows = kSlabRows * rpg;
+  const int panels = (m + rows - 1) / rows;
   const int tiles = (n + kSlabTile - 1) / kSlabTile;
-  const int tpw = slab_tiles_per_wg(m, n);
+  const int tpw = slab_tiles_per_wg(panels, tiles);
   const int groups = (tiles + tpw - 1) / tpw;
-  info->variant = kSpmmSlab;
+  info->variant = variant;
   info->vec = 4;
   info->lanes_per_row = 16;
-  info->rows_per_block = kSlabRows;
+  info->rows_per_block = rows;
   info->block_threads = kSlabThreads;
   info->grid_x = ((panels + 7) / 8) * 8 * groups;
   info->grid_y = tpw;                       // tiles walked by one workgroup (the grid is 1-D)
@@ -111,8 +118,7 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
                   ? kSpmmSlabDma : kSpmmRowsplit;
   }
   if ((variant == kSpmmSlab || variant == kSpmmSlabDma) && sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C)) {
-    fill_spmm_slab_info(m, n, info);
-    info->variant = variant;
+    fill_spmm_slab_info(m, n, variant, info);
   } else {
     fill_spmm_rowsplit_info<T>(m, n, B, C, info);
   }
@@ -161,23 +167,24 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const 
     if constexpr (sizeof(T) == 4) {
       static std::atomic<bool> configured{false};
       auto kernel = spmm_slab_kernel<T, kSlabS>;
-      auto kernel_dma = spmm_slab_dma_kernel<kSlabS>;
+      auto kernel_dma1 = spmm_slab_dma_kernel<kSlabS, 1>;
+      auto kernel_dma2 = spmm_slab_dma_kernel<kSlabS, 2>;
       if (!configured.load()) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kSlabLdsBytes) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(kernel_dma),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kSlabLdsBytes) != hipSuccess)
-          return SPDL_ERR_LAUNCH;
+        for (const void* f : {reinterpret_cast<const void*>(kernel), reinterpret_cast<const void*>(kernel_dma1),
+                              reinterpret_cast<const void*>(kernel_dma2)})
+          if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kSlabLdsBytes) != hipSuccess)
+            return SPDL_ERR_LAUNCH;
         configured.store(true);
       }
-      const int panels = (m + kSlabRows - 1) / kSlabRows;
+      const int panels = (m + li.rows_per_block - 1) / li.rows_per_block;
       const int tiles = (n + kSlabTile - 1) / kSlabTile;
+      const dim3 grid(li.grid_x), block(kSlabThreads);
       if (li.variant == kSpmmSlab)
-        kernel<<<dim3(li.grid_x), dim3(kSlabThreads), kSlabLdsBytes, st>>>(m, k, n, nnz, tiles, li.grid_y, panels,
-                                                                          ro, ci, val, order, B, C);
+        kernel<<<grid, block, kSlabLdsBytes, st>>>(m, k, n, nnz, tiles, li.grid_y, panels, ro, ci, val, order, B, C);
+      else if (li.rows_per_block == kSlabRows)
+        kernel_dma1<<<grid, block, kSlabLdsBytes, st>>>(m, k, n, nnz, tiles, li.grid_y, panels, ro, ci, val, order, B, C);
       else
-        kernel_dma<<<dim3(li.grid_x), dim3(kSlabThreads), kSlabLdsBytes, st>>>(m, k, n, nnz, tiles, li.grid_y,
-                                                                              panels, ro, ci, val, order, B, C);
+        kernel_dma2<<<grid, block, kSlabLdsBytes, st>>>(m, k, n, nnz, tiles, li.grid_y, panels, ro, ci, val, order, B, C);
     } else {
       return SPDL_ERR_UNSUPPORTED;
     }

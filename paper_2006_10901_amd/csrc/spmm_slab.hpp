@@ -58,6 +58,28 @@ constexpr int kSlabConsumers = 512;    // threads of the consumer waves
   SPDL_DPP_FMA4(T2, BQ[2], "")                                                                 \
   SPDL_DPP_FMA4(T3, BQ[3], "")
 
+// The up to 16 steps of one round: pair t of every group (value av, LDS offset off, both held
+// by lane t of the group) times its B row, for t < cmax rounded up to a multiple of four.
+// The reads one group of four ahead are issued whether or not that group is needed (every
+// offset is a valid LDS address), so that the wait before each block of multiply-adds can
+// leave exactly the younger four reads outstanding.
+__device__ __forceinline__ void slab_steps(float (&acc)[4], float av, int off, const char* buf, int lane_b,
+                                           int cmax) {
+  f32x4 bx[4], by[4];
+  SPDL_DPP_LOAD4(bx, 0, 1, 2, 3)
+  SPDL_DPP_LOAD4(by, 4, 5, 6, 7)
+  SPDL_DPP_FMA16(bx, 0, 1, 2, 3, "s_nop 1\n\t")
+  if (cmax > 4) {
+    SPDL_DPP_LOAD4(bx, 8, 9, 10, 11)
+    SPDL_DPP_FMA16(by, 4, 5, 6, 7, "")
+    if (cmax > 8) {
+      SPDL_DPP_LOAD4(by, 12, 13, 14, 15)
+      SPDL_DPP_FMA16(bx, 8, 9, 10, 11, "")
+      if (cmax > 12) { SPDL_DPP_FMA16(by, 12, 13, 14, 15, "") }
+    }
+  }
+}
+
 // State of one sparse row inside a 16-lane group.
 struct SlabRow {
   int row, p_begin, p, row_end;
