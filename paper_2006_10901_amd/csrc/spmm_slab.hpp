@@ -52,11 +52,30 @@ constexpr int kSlabConsumers = 512;    // threads of the consumer waves
   BQ[2] = *reinterpret_cast<const f32x4*>(buf + SPDL_DPP_ADDR(T2));                            \
   BQ[3] = *reinterpret_cast<const f32x4*>(buf + SPDL_DPP_ADDR(T3));
 
-#define SPDL_DPP_FMA16(BQ, T0, T1, T2, T3, PRE)                                                \
-  SPDL_DPP_FMA4(T0, BQ[0], PRE)                                                                \
-  SPDL_DPP_FMA4(T1, BQ[1], "")                                                                 \
-  SPDL_DPP_FMA4(T2, BQ[2], "")                                                                 \
-  SPDL_DPP_FMA4(T3, BQ[3], "")
+// One asm statement per group, so that the wait in front of it can leave exactly the four
+// younger reads of the next group outstanding.
+#define SPDL_DPP_FMA16(BQ, T0, T1, T2, T3, PRE)                                                              \
+  asm volatile(PRE                                                                                            \
+               "v_fmac_f32_dpp %0, %4, %5 row_newbcast:" #T0 " row_mask:0xf bank_mask:0xf\n\t"                \
+               "v_fmac_f32_dpp %1, %4, %6 row_newbcast:" #T0 " row_mask:0xf bank_mask:0xf\n\t"                \
+               "v_fmac_f32_dpp %2, %4, %7 row_newbcast:" #T0 " row_mask:0xf bank_mask:0xf\n\t"                \
+               "v_fmac_f32_dpp %3, %4, %8 row_newbcast:" #T0 " row_mask:0xf bank_mask:0xf\n\t"                \
+               "v_fmac_f32_dpp %0, %4, %9 row_newbcast:" #T1 " row_mask:0xf bank_mask:0xf\n\t"                \
+               "v_fmac_f32_dpp %1, %4, %10 row_newbcast:" #T1 " row_mask:0xf bank_mask:0xf\n\t"               \
+               "v_fmac_f32_dpp %2, %4, %11 row_newbcast:" #T1 " row_mask:0xf bank_mask:0xf\n\t"               \
+               "v_fmac_f32_dpp %3, %4, %12 row_newbcast:" #T1 " row_mask:0xf bank_mask:0xf\n\t"               \
+               "v_fmac_f32_dpp %0, %4, %13 row_newbcast:" #T2 " row_mask:0xf bank_mask:0xf\n\t"               \
+               "v_fmac_f32_dpp %1, %4, %14 row_newbcast:" #T2 " row_mask:0xf bank_mask:0xf\n\t"               \
+               "v_fmac_f32_dpp %2, %4, %15 row_newbcast:" #T2 " row_mask:0xf bank_mask:0xf\n\t"               \
+               "v_fmac_f32_dpp %3, %4, %16 row_newbcast:" #T2 " row_mask:0xf bank_mask:0xf\n\t"               \
+               "v_fmac_f32_dpp %0, %4, %17 row_newbcast:" #T3 " row_mask:0xf bank_mask:0xf\n\t"               \
+               "v_fmac_f32_dpp %1, %4, %18 row_newbcast:" #T3 " row_mask:0xf bank_mask:0xf\n\t"               \
+               "v_fmac_f32_dpp %2, %4, %19 row_newbcast:" #T3 " row_mask:0xf bank_mask:0xf\n\t"               \
+               "v_fmac_f32_dpp %3, %4, %20 row_newbcast:" #T3 " row_mask:0xf bank_mask:0xf"                    \
+               : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])                                       \
+               : "v"(av), "v"(BQ[0].x), "v"(BQ[0].y), "v"(BQ[0].z), "v"(BQ[0].w), "v"(BQ[1].x), "v"(BQ[1].y), \
+                 "v"(BQ[1].z), "v"(BQ[1].w), "v"(BQ[2].x), "v"(BQ[2].y), "v"(BQ[2].z), "v"(BQ[2].w),          \
+                 "v"(BQ[3].x), "v"(BQ[3].y), "v"(BQ[3].z), "v"(BQ[3].w));
 
 // The up to 16 steps of one round: pair t of every group (value av, LDS offset off, both held
 // by lane t of the group) times its B row, for t < cmax rounded up to a multiple of four.
