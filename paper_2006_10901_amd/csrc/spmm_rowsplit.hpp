@@ -9,14 +9,20 @@ namespace spdl {
 
 template <typename T, int VEC, int G>
 __global__ __launch_bounds__(256) void spmm_rowsplit_kernel(
-    int m, int n, const int* __restrict__ row_offsets, const int* __restrict__ column_indices,
-    const T* __restrict__ values, const int* __restrict__ row_order, const T* __restrict__ B,
-    T* __restrict__ C) {
+    int m, int n, const int* __restrict__ row_offsets,
+    const int* __restrict__ column_indices, const T* __restrict__ values, const int* __restrict__ row_order,
+    const T* __restrict__ B, T* __restrict__ C) {
   constexpr int ROWS = 256 / G;
-  constexpr int U = 8;
+  constexpr int U = (G == kWave && VEC * sizeof(T) <= 16) ? 16 : 8;   // nonzeros in flight per lane
   const int sub = threadIdx.x / G;
   const int lane = threadIdx.x % G;
-  const int slot = blockIdx.x * ROWS + sub;
+  // Row binning and bundling (paper Sec. "Row Swizzle Load Balancing"): the rows of one wave
+  // are adjacent in the row order (a bundle of similar lengths, so the lanes of a wave finish
+  // together), while the four waves of a block take bundles a quarter of the order apart, so
+  // every block, and with it every CU, gets the same mix of long and short rows.
+  constexpr int RPW = kWave / G;                       // rows per wave
+  const int wave_in_block = threadIdx.x / kWave;
+  const int slot = (wave_in_block * (int)gridDim.x + (int)blockIdx.x) * RPW + sub % RPW;
   if (slot >= m) return;
   int row = row_order ? row_order[slot] : slot;          // row swizzle: one extra load
   if (G == kWave) row = uniform(row);                    // whole wave on one row: scalar loads

@@ -264,7 +264,8 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_kernel(
   SlabRow rows[2];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    const int slot = panel * kSlabRows + (wave * 4 + sub) * 2 + j;
+    // a wave's 8 rows are adjacent in the row order; a workgroup takes every panels-th bundle
+    const int slot = ((wave * panels + panel) * 4 + sub) * 2 + j;
     rows[j].row = -1;
     rows[j].p_begin = rows[j].row_end = 0;
     if (slot < m) {

@@ -76,7 +76,10 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_dma_kernel(
   SlabRow rows[RPG];
 #pragma unroll
   for (int j = 0; j < RPG; ++j) {
-    const int slot = panel * (kSlabRows * RPG) + (wave * 4 + sub) * RPG + j;
+    // Row binning (paper Sec. "Row Swizzle Load Balancing"): a wave's 4*RPG rows are adjacent
+    // in the row order (a bundle of similar lengths), and a workgroup takes every panels-th
+    // bundle, so each workgroup gets the same mix of long and short bundles.
+    const int slot = ((wave * panels + panel) * 4 + sub) * RPG + j;
     rows[j].row = -1;
     rows[j].p_begin = rows[j].row_end = 0;
     if (slot < m) {
