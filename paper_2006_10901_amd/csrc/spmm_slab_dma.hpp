@@ -5,13 +5,13 @@
 // next slab with direct-to-LDS loads (no staging registers, no LDS store instructions).
 //
 // A wait for sparse elements that were requested after the slab copies also waits for the
-// copies, so waits inside a stage are avoided: the kernel works in double rounds of 32
-// (value, column) pairs per row, the next 32 pairs are requested as soon as the cursor is
-// known, before the arithmetic of the current double round, and they are first needed in the
+// copies, so waits inside a stage are avoided: the kernel works in long rounds of 16*NCH
+// (value, column) pairs per row, the next pairs are requested as soon as the cursor is
+// known, before the arithmetic of the current round, and they are first needed in the
 // next stage.  The only wait is the one at the end of a stage, for everything (copies and pair
 // loads alike have had the stage's arithmetic to complete); no assumption is made about the
-// order in which copies and ordinary loads retire.  A row with more than 32 pairs in a slab
-// takes further double rounds, each behind a full wait.
+// order in which copies and ordinary loads retire.  A row with more than 16*NCH pairs in a
+// slab takes further rounds, each behind a full wait.
 #pragma once
 #include "common.hpp"
 #include "spmm_slab.hpp"
@@ -21,7 +21,9 @@ namespace spdl {
 // RPG = sparse rows per 16-lane group (1 or 2): the workgroup owns 64*RPG rows.  Two rows per
 // group halve the traffic of B and the number of stages per unit of work when the output has
 // enough tiles to fill the machine anyway.
-template <int S, int RPG>
+// NCH = chunks of 16 pairs fetched ahead per row (chosen by the host from the density so that
+// a row's pairs inside one slab usually fit).
+template <int S, int RPG, int NCH>
 __global__ __launch_bounds__(kSlabThreads) void spmm_slab_dma_kernel(
     int m, int k, int n, int nnz, int tiles_n, int tiles_per_wg, int panels,
     const int* __restrict__ row_offsets, const int* __restrict__ column_indices,
@@ -93,64 +95,69 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_dma_kernel(
   const int sub8 = sub * 8;
   float acc[RPG][4];
 
-  // Pairs [at, at+16) and [at+16, at+32) of each row, lane t of the group holding pair t.  The
-  // loaded words are kept raw (no arithmetic on them here): the compiler waits for a load at
-  // its first use, and the first use is in the next stage, after the full wait that ends
-  // every stage.  32-bit byte offsets from scalar bases (nnz < 2^29 is checked on the host).
-  int cA[RPG], cB[RPG], at[RPG];
-  float aA[RPG], aB[RPG];
-  auto fetch32 = [&](int j, int from) {
+  // The next 16*NCH pairs of each row from position `at`, chunk i holding pairs
+  // [at + 16 i, at + 16 i + 16), lane t of the group holding pair t.  The loaded words are kept
+  // raw (no arithmetic on them here): the compiler waits for a load at its first use, and the
+  // first use is in the next stage, after the full wait that ends every stage.  32-bit byte
+  // offsets from scalar bases (nnz < 2^29 is checked on the host).
+  int cc[RPG][NCH], at[RPG];
+  float aa[RPG][NCH];
+  auto fetch_pairs = [&](int j, int from) {
     at[j] = from;
-    const int idx = from + l16;
-    const unsigned oa = (unsigned)min(idx, last_nz) << 2, ob = (unsigned)min(idx + 16, last_nz) << 2;
     const char* cbase = reinterpret_cast<const char*>(column_indices);
     const char* vbase = reinterpret_cast<const char*>(values);
-    cA[j] = *reinterpret_cast<const int*>(cbase + oa);
-    aA[j] = *reinterpret_cast<const float*>(vbase + oa);
-    cB[j] = *reinterpret_cast<const int*>(cbase + ob);
-    aB[j] = *reinterpret_cast<const float*>(vbase + ob);
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const unsigned o = (unsigned)min(from + l16 + 16 * i, last_nz) << 2;
+      cc[j][i] = *reinterpret_cast<const int*>(cbase + o);
+      aa[j][i] = *reinterpret_cast<const float*>(vbase + o);
+    }
   };
   // every vector-memory operation of this wave (pair loads, slab copies) has completed
   auto wait_everything = [&]() { __builtin_amdgcn_s_waitcnt(0); };
 
-  // One double round of row j in the slab starting at slab_start.  Returns true when all 32
-  // fetched pairs of some group were used, i.e. the slab may hold more pairs of that row.
+  // One long round of row j in the slab starting at slab_start: the leading pairs of the
+  // fetched 16*NCH that fall into the slab.  Returns true when all of them were used by some
+  // group, i.e. the slab may hold more pairs of that row.
   // `restart`: this is the last slab of a tile and another tile follows, so once the row is done
   // here the next pairs needed are those at the row start again.
-  auto double_round = [&](int j, const char* buf, int slab_start, bool restart) -> bool {
+  auto long_round = [&](int j, const char* buf, int slab_start, bool restart) -> bool {
     const int idx = at[j] + l16;
-    const unsigned relA = (unsigned)(cA[j] - slab_start), relB = (unsigned)(cB[j] - slab_start);
-    const bool inA = idx < rows[j].row_end && relA < (unsigned)S;
-    const unsigned long long mA = __ballot(inA);
-    const unsigned lo = (unsigned)mA, hi = (unsigned)(mA >> 32);
-    const int a0 = leading16(lo & 0xffffu), a1 = leading16(lo >> 16);
-    const int a2 = leading16(hi & 0xffffu), a3 = leading16(hi >> 16);
-    const int cmaxA = max(max(a0, a1), max(a2, a3));
-    const unsigned packedA = (unsigned)a0 | ((unsigned)a1 << 8) | ((unsigned)a2 << 16) | ((unsigned)a3 << 24);
-    const int cntA = (int)((packedA >> sub8) & 0xffu);
-    // the second 16 continue the first 16 only where those were all consumed
-    const bool inB = cntA == 16 && idx + 16 < rows[j].row_end && relB < (unsigned)S;
-    const unsigned long long mB = __ballot(inB);
-    const unsigned lo2 = (unsigned)mB, hi2 = (unsigned)(mB >> 32);
-    const int b0 = leading16(lo2 & 0xffffu), b1 = leading16(lo2 >> 16);
-    const int b2 = leading16(hi2 & 0xffffu), b3 = leading16(hi2 >> 16);
-    const int cmaxB = max(max(b0, b1), max(b2, b3));
-    const unsigned packedB = (unsigned)b0 | ((unsigned)b1 << 8) | ((unsigned)b2 << 16) | ((unsigned)b3 << 24);
-    const int cntB = (int)((packedB >> sub8) & 0xffu);
-    const float avA = inA ? aA[j] : 0.f, avB = inB ? aB[j] : 0.f;
-    const int offA = inA ? (int)(relA * (kSlabTile * 4)) : kZeroOff;
-    const int offB = inB ? (int)(relB * (kSlabTile * 4)) : kZeroOff;
-    rows[j].p += cntA + cntB;
-    // next 32 pairs, first needed in the next stage (or in the next double round of this one)
-    fetch32(j, (restart && cmaxB < 16) ? rows[j].p_begin : rows[j].p);
-    if (cmaxA > 0) slab_steps(acc[j], avA, offA, buf, lane_b, cmaxA);
-    if (cmaxB > 0) slab_steps(acc[j], avB, offB, buf, lane_b, cmaxB);
-    return cmaxB == 16;
+    float av[NCH];
+    int off[NCH], cmax[NCH];
+    int total = 0, prev_cnt = 16;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      // chunk i continues chunk i-1 only where that one was consumed completely
+      const unsigned rel = (unsigned)(cc[j][i] - slab_start);
+      const bool in = prev_cnt == 16 && idx + 16 * i < rows[j].row_end && rel < (unsigned)S;
+      // everything derived from the wave mask is wave-uniform and stays in scalar registers
+      const unsigned long long mk = __ballot(in);
+      const unsigned lo = (unsigned)mk, hi = (unsigned)(mk >> 32);
+      const int c0 = leading16(lo & 0xffffu), c1 = leading16(lo >> 16);
+      const int c2 = leading16(hi & 0xffffu), c3 = leading16(hi >> 16);
+      cmax[i] = max(max(c0, c1), max(c2, c3));
+      const unsigned packed = (unsigned)c0 | ((unsigned)c1 << 8) | ((unsigned)c2 << 16) | ((unsigned)c3 << 24);
+      prev_cnt = (int)((packed >> sub8) & 0xffu);
+      total += prev_cnt;
+      // a pair inside the slab is used even if it is not among the leading ones (rows that
+      // are not ascending): the cursor then stops short of the row end and the row is redone
+      av[i] = in ? aa[j][i] : 0.f;
+      off[i] = in ? (int)(rel * (kSlabTile * 4)) : kZeroOff;
+    }
+    rows[j].p += total;
+    const bool more = cmax[NCH - 1] == 16;
+    // the next pairs, first needed in the next stage (or in the next long round of this one)
+    fetch_pairs(j, (restart && !more) ? rows[j].p_begin : rows[j].p);
+#pragma unroll
+    for (int i = 0; i < NCH; ++i)
+      if (cmax[i] > 0) slab_steps(acc[j], av[i], off[i], buf, lane_b, cmax[i]);
+    return more;
   };
 
   copy_stage(0);
 #pragma unroll
-  for (int j = 0; j < RPG; ++j) fetch32(j, rows[j].p_begin);
+  for (int j = 0; j < RPG; ++j) fetch_pairs(j, rows[j].p_begin);
   wait_everything();
   __builtin_amdgcn_s_barrier();
   int q = 0;
@@ -166,16 +173,16 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_dma_kernel(
       // A use of the youngest pair register before the copies are issued: the compiler places
       // its wait for the pair loads here, where they completed long ago (full wait at the end
       // of the previous stage), instead of after the copies, where it would wait for those too.
-      asm volatile("v_mov_b32 %0, %0" : "+v"(aB[RPG - 1]));
+      asm volatile("v_mov_b32 %0, %0" : "+v"(aa[RPG - 1][NCH - 1]));
       if (q + 1 < stages) copy_stage(q + 1);
       const char* buf = lds_raw + (q & 1) * kBufBytes;
 #pragma unroll
       for (int j = 0; j < RPG; ++j) {
         const bool restart = s == nslabs - 1 && tile + 1 < tile_end;
-        // The first double round stands outside the loop: inside it the compiler would have to
+        // The first long round stands outside the loop: inside it the compiler would have to
         // wait for the previous iteration's loads, and with them for the copies just issued.
-        if (double_round(j, buf, s * S, restart))
-          while (double_round(j, buf, s * S, restart)) {}        // more than 32 pairs in this slab
+        if (long_round(j, buf, s * S, restart))
+          while (long_round(j, buf, s * S, restart)) {}          // more than 16*NCH pairs in this slab
       }
       wait_everything();
       __builtin_amdgcn_s_barrier();
