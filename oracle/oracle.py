@@ -100,3 +100,39 @@ def row_order(m, row_offsets):
     out = np.empty(m, dtype=np.int32)
     lib.oracle_row_order(m, _p(ro), _p(out))
     return out
+
+
+def csr_softmax(m, row_offsets, x, scale=1.0):
+    """Paper Sec. 'Application: Sparse Transformer': softmax over the stored entries of each row."""
+    lib = _load()
+    ro = np.ascontiguousarray(row_offsets, dtype=np.int32)
+    xv = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.zeros(xv.shape[0], dtype=np.float64)
+    lib.oracle_csr_softmax_f32(m, _p(ro), _p(xv), ctypes.c_double(scale), _p(out))
+    return out
+
+
+def spmm_bias_relu(m, k, n, row_offsets, column_indices, values, B, bias):
+    """Paper Sec. 'Application: Sparse MobileNetV1': C = relu(A B + bias[row])."""
+    lib = _load()
+    ro, ci = _csr_args(row_offsets, column_indices)
+    v = np.ascontiguousarray(values, dtype=np.float32)
+    b = np.ascontiguousarray(B, dtype=np.float32)
+    bs = np.ascontiguousarray(bias, dtype=np.float32)
+    assert bs.shape == (m,) and b.shape == (k, n)
+    C = np.empty((m, n), dtype=np.float64)
+    S = np.empty((m, n), dtype=np.float64)
+    lib.oracle_spmm_bias_relu_f32(m, k, n, _p(ro), _p(ci), _p(v), _p(b), _p(bs), _p(C), _p(S))
+    return C, S
+
+
+def transpose_topology(m, k, row_offsets, column_indices):
+    """Paper Sec. 'Discussion & Conclusion': topology of A^T and the permutation that moves the values."""
+    lib = _load()
+    ro, ci = _csr_args(row_offsets, column_indices)
+    nnz = ci.shape[0]
+    tro = np.empty(k + 1, dtype=np.int32)
+    tci = np.empty(nnz, dtype=np.int32)
+    perm = np.empty(nnz, dtype=np.int32)
+    lib.oracle_transpose_topology(m, k, _p(ro), _p(ci), _p(tro), _p(tci), _p(perm))
+    return tro, tci, perm

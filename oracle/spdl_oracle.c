@@ -158,3 +158,60 @@ void oracle_row_order(int m, const int32_t* row_offsets, int32_t* row_order) {
   }
   free(start);
 }
+
+/* Softmax over the stored entries of every CSR row, on scaled logits (paper Sec. "Application:
+ * Sparse Transformer": softmax(Q K^T / sqrt(d_k)) restricted to the sparse topology):
+ *   out[p] = exp(scale*x[p] - M_i) / sum_q exp(scale*x[q] - M_i),  M_i = max_q scale*x[q],
+ * q ranging over the entries of the row that holds p.  Rows without entries produce nothing.
+ * Double precision throughout; the maximum is subtracted as in the textbook formulation. */
+void oracle_csr_softmax_f32(int m, const int32_t* row_offsets, const float* x, double scale, double* out) {
+#pragma omp parallel for schedule(dynamic, 64)
+  for (int i = 0; i < m; ++i) {
+    const int s = row_offsets[i], e = row_offsets[i + 1];
+    if (e <= s) continue;
+    double mx = scale * (double)x[s];
+    for (int p = s + 1; p < e; ++p) {
+      double v = scale * (double)x[p];
+      if (v > mx) mx = v;
+    }
+    double sum = 0.0;
+    for (int p = s; p < e; ++p) sum += exp(scale * (double)x[p] - mx);
+    for (int p = s; p < e; ++p) out[p] = exp(scale * (double)x[p] - mx) / sum;
+  }
+}
+
+/* Fused epilogue of the sparse 1x1 convolution (paper Sec. "Application: Sparse MobileNetV1":
+ * bias and ReLU fused into the SpMM):  C[i,j] = max(0, sum_p values[p]*B[col[p],j] + bias[i]).
+ * S[i,j] = sum_p |product| + |bias[i]| is the tolerance scale. */
+void oracle_spmm_bias_relu_f32(int m, int k, int n, const int32_t* row_offsets, const int32_t* column_indices,
+                               const float* values, const float* B, const float* bias, double* C, double* S) {
+  oracle_spmm_f32(m, k, n, row_offsets, column_indices, values, B, C, S);
+#pragma omp parallel for
+  for (int i = 0; i < m; ++i)
+    for (int j = 0; j < n; ++j) {
+      double v = C[(size_t)i * n + j] + (double)bias[i];
+      C[(size_t)i * n + j] = v > 0.0 ? v : 0.0;
+      S[(size_t)i * n + j] += fabs((double)bias[i]);
+    }
+}
+
+/* Transposed topology for A^T B (paper Sec. "Discussion & Conclusion": cache the row offsets
+ * and column indices of A^T when the topology changes and move the values with a permutation).
+ * Entry p of A at (i, c) becomes an entry of row c of A^T with column i; within a row of A^T
+ * entries are ordered by ascending i (the order in which a row-major scan of A meets them).
+ * perm[t] = position in A of the t-th entry of A^T. */
+void oracle_transpose_topology(int m, int k, const int32_t* row_offsets, const int32_t* column_indices,
+                               int32_t* t_row_offsets, int32_t* t_column_indices, int32_t* perm) {
+  for (int c = 0; c <= k; ++c) t_row_offsets[c] = 0;
+  for (int p = 0; p < row_offsets[m]; ++p) t_row_offsets[column_indices[p] + 1]++;
+  for (int c = 0; c < k; ++c) t_row_offsets[c + 1] += t_row_offsets[c];
+  int32_t* cursor = (int32_t*)malloc(sizeof(int32_t) * (size_t)(k > 0 ? k : 1));
+  for (int c = 0; c < k; ++c) cursor[c] = t_row_offsets[c];
+  for (int i = 0; i < m; ++i)
+    for (int p = row_offsets[i]; p < row_offsets[i + 1]; ++p) {
+      int t = cursor[column_indices[p]]++;
+      t_column_indices[t] = i;
+      perm[t] = p;
+    }
+  free(cursor);
+}

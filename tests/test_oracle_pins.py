@@ -192,3 +192,56 @@ def test_row_order_is_stable_descending_permutation(oracle_lib):
     same = np.diff(lens[order]) == 0
     assert np.all(np.diff(order)[same] > 0)                          # ties: ascending row index
     assert np.array_equal(order, np.argsort(-lens, kind="stable"))  # library stable sort
+
+
+# ------------------------------------------------------------------ rows added after the hot path
+def test_csr_softmax_against_library_and_closed_forms(oracle_lib):
+    from scipy.special import softmax as lib_softmax
+    A = wl.adversarial_csr(60, 90, 91)
+    x = np.random.default_rng(92).standard_normal(A.nnz).astype(np.float32) * 3
+    for scale in (1.0, 0.125):
+        out = oracle_lib.csr_softmax(A.m, A.row_offsets, x, scale)
+        for i in range(A.m):
+            s, e = A.row_offsets[i], A.row_offsets[i + 1]
+            if e > s:
+                assert np.allclose(out[s:e], lib_softmax(scale * x[s:e].astype(np.float64)), rtol=1e-12, atol=0)
+                assert abs(out[s:e].sum() - 1.0) < 1e-12
+    # equal logits -> 1/len; two entries -> logistic closed form; shift invariance
+    ro = np.array([0, 5, 7, 7, 8], dtype=np.int32)
+    v = np.array([2, 2, 2, 2, 2, 1.5, -0.25, 9.0], dtype=np.float32)
+    out = oracle_lib.csr_softmax(4, ro, v, 1.0)
+    assert np.allclose(out[:5], 0.2, rtol=1e-15)
+    assert np.isclose(out[5], 1.0 / (1.0 + np.exp(-0.25 - 1.5)), rtol=1e-14) and np.isclose(out[5] + out[6], 1.0)
+    assert out[7] == 1.0
+    shifted = oracle_lib.csr_softmax(4, ro, v + np.float32(4.0), 1.0)       # exact shift in fp32 here
+    assert np.allclose(shifted, out, rtol=1e-13)
+    big = oracle_lib.csr_softmax(1, np.array([0, 3], np.int32), np.array([1000, 999, -1000], np.float32), 1.0)
+    assert np.all(np.isfinite(big)) and np.isclose(big[0], 1 / (1 + np.exp(-1.0)), rtol=1e-12) and big[2] == 0.0
+
+
+def test_spmm_bias_relu_against_dense(oracle_lib):
+    A = wl.uniform_mask_csr(30, 44, 0.3, 93)
+    B = wl.dense(44, 13, 94)
+    bias = np.random.default_rng(95).standard_normal(30).astype(np.float32)
+    C, S = oracle_lib.spmm_bias_relu(30, 44, 13, A.row_offsets, A.column_indices, A.values, B, bias)
+    ref = np.maximum(densify(A) @ B.astype(np.float64) + bias.astype(np.float64)[:, None], 0.0)
+    assert np.allclose(C, ref, rtol=1e-12, atol=1e-12)
+    assert (C == 0).any() and (C > 0).any()
+    plain, S0 = oracle_lib.spmm(30, 44, 13, A.row_offsets, A.column_indices, A.values, B)
+    assert np.allclose(S, S0 + np.abs(bias.astype(np.float64))[:, None], rtol=1e-13)
+    zero_bias, _ = oracle_lib.spmm_bias_relu(30, 44, 13, A.row_offsets, A.column_indices, A.values, B, np.zeros(30, np.float32))
+    assert np.array_equal(zero_bias, np.maximum(plain, 0.0))
+
+
+def test_transpose_topology_and_transposed_spmm(oracle_lib):
+    A = wl.adversarial_csr(37, 53, 96)
+    tro, tci, perm = oracle_lib.transpose_topology(A.m, A.k, A.row_offsets, A.column_indices)
+    assert tro[0] == 0 and tro[-1] == A.nnz and sorted(perm.tolist()) == list(range(A.nnz))
+    D = densify(A)
+    T = wl.Csr(A.k, A.m, tro, tci, A.values[perm])
+    assert np.array_equal(densify(T), D.T)                         # same matrix, transposed
+    for c in range(A.k):
+        assert np.all(np.diff(tci[tro[c]:tro[c + 1]]) > 0)         # ascending inside each row of A^T
+    B = wl.dense(A.m, 9, 97)
+    C, _ = oracle_lib.spmm(A.k, A.m, 9, tro, tci, T.values, B)
+    assert np.allclose(C, D.T @ B.astype(np.float64), rtol=1e-12, atol=1e-12)
