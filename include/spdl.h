@@ -66,6 +66,51 @@ int spdl_spmm_f16(int m, int k, int n, int nnz, const int* row_offsets, const in
 int spdl_sddmm_f16(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                    const uint16_t* L, const uint16_t* R, uint16_t* out_values, void* stream);
 
+/* SpMM with a fused epilogue (paper Sec. "Application: Sparse MobileNetV1": bias and ReLU are
+ * fused into the sparse 1x1 convolution, whose weights are the sparse matrix and whose rows
+ * are the output channels):
+ *   C[i,j] = act( sum_p values[p] * B[column_indices[p], j] + bias[i] ),  act = max(., 0) when
+ *   relu != 0, identity otherwise.
+ *   bias : DEVICE [m], one value per row of A; NULL = no bias.  Everything else as spdl_spmm.
+ *   The sum is formed exactly as in spdl_spmm, the bias is added to it in fp32, and in the fp16
+ *   version the result is rounded to binary16 once, after the activation. */
+int spdl_spmm_bias_relu(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                        const float* values, const int* row_order, const float* B, const float* bias,
+                        int relu, float* C, void* stream);
+int spdl_spmm_bias_relu_f16(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                            const uint16_t* values, const int* row_order, const uint16_t* B,
+                            const uint16_t* bias, int relu, uint16_t* C, void* stream);
+
+/* Softmax over the stored entries of each row of a CSR matrix (paper Sec. "Application: Sparse
+ * Transformer": the attention weights are the softmax of the sampled, scaled scores):
+ *   probabilities[p] = exp(scale*logits[p] - M_i) / sum_q exp(scale*logits[q] - M_i),
+ *   q over the entries of the row i that holds p, M_i = max_q scale*logits[q].
+ *   row_offsets : DEVICE int32[m+1];  logits : DEVICE fp32[nnz];  probabilities : DEVICE
+ *   fp32[nnz], fully overwritten, may be the same array as logits.  Empty rows produce nothing.
+ *   A row that holds +inf or NaN produces NaN in that row (as the definition does). */
+int spdl_csr_softmax(int m, int nnz, const int* row_offsets, const float* logits, float scale,
+                     float* probabilities, void* stream);
+
+/* Topology of the transpose (paper Sec. "Discussion & Conclusion": with a fixed topology the
+ * transposed offsets and indices are computed once and cached, and the transposed values are
+ * a permutation of the values).  Pure host code.
+ *   row_offsets_host, column_indices_host : HOST, CSR topology of A (m x k, nnz entries)
+ *   t_row_offsets_host : HOST int32[k+1], t_column_indices_host : HOST int32[nnz], written: the
+ *     CSR topology of A^T (k x m); inside a row of A^T the entries are in ascending row index
+ *     of A (entries of equal row in their stored order).
+ *   perm_host : HOST int32[nnz], written: entry t of A^T is entry perm[t] of A.
+ *   Returns SPDL_ERR_BAD_CSR when the input is not a valid topology (nothing defined is written). */
+int spdl_build_transpose_host(int m, int k, int nnz, const int* row_offsets_host,
+                              const int* column_indices_host, int* t_row_offsets_host,
+                              int* t_column_indices_host, int* perm_host);
+
+/* out[t] = values[perm[t]] for t in [0,nnz): the values of A^T from those of A (same passage).
+ *   perm : DEVICE int32[nnz], each in [0,nnz);  values, out : DEVICE, nnz elements of elem_bytes
+ *   (2 or 4) bytes each, distinct arrays.  With the arrays of spdl_build_transpose_host,
+ *   spdl_spmm on (k, m, t_row_offsets, t_column_indices, out) computes A^T B. */
+int spdl_permute_values(int nnz, int elem_bytes, const int* perm, const void* values, void* out,
+                        void* stream);
+
 /* Row swizzle (paper Sec. "Row Binning & Row Bundling Heuristics"): row indices sorted by
  * decreasing row length, equal lengths in ascending row index.  Pure host code.
  *   row_offsets_host : HOST int32[m+1];   row_order_host : HOST int32[m], written. */

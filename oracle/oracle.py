@@ -112,17 +112,19 @@ def csr_softmax(m, row_offsets, x, scale=1.0):
     return out
 
 
-def spmm_bias_relu(m, k, n, row_offsets, column_indices, values, B, bias):
-    """Paper Sec. 'Application: Sparse MobileNetV1': C = relu(A B + bias[row])."""
+def spmm_bias_relu(m, k, n, row_offsets, column_indices, values, B, bias, relu=True):
+    """Paper Sec. 'Application: Sparse MobileNetV1': C = relu(A B + bias[row]); bias None adds
+    nothing, relu False leaves the sum as it is."""
     lib = _load()
     ro, ci = _csr_args(row_offsets, column_indices)
     v = np.ascontiguousarray(values, dtype=np.float32)
     b = np.ascontiguousarray(B, dtype=np.float32)
-    bs = np.ascontiguousarray(bias, dtype=np.float32)
-    assert bs.shape == (m,) and b.shape == (k, n)
+    bs = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    assert (bs is None or bs.shape == (m,)) and b.shape == (k, n)
     C = np.empty((m, n), dtype=np.float64)
     S = np.empty((m, n), dtype=np.float64)
-    lib.oracle_spmm_bias_relu_f32(m, k, n, _p(ro), _p(ci), _p(v), _p(b), _p(bs), _p(C), _p(S))
+    lib.oracle_spmm_bias_relu_f32(m, k, n, _p(ro), _p(ci), _p(v), _p(b), _p(bs) if bs is not None else None,
+                                  int(bool(relu)), _p(C), _p(S))
     return C, S
 
 

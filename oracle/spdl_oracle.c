@@ -184,14 +184,16 @@ void oracle_csr_softmax_f32(int m, const int32_t* row_offsets, const float* x, d
  * bias and ReLU fused into the SpMM):  C[i,j] = max(0, sum_p values[p]*B[col[p],j] + bias[i]).
  * S[i,j] = sum_p |product| + |bias[i]| is the tolerance scale. */
 void oracle_spmm_bias_relu_f32(int m, int k, int n, const int32_t* row_offsets, const int32_t* column_indices,
-                               const float* values, const float* B, const float* bias, double* C, double* S) {
+                               const float* values, const float* B, const float* bias, int relu, double* C,
+                               double* S) {
   oracle_spmm_f32(m, k, n, row_offsets, column_indices, values, B, C, S);
 #pragma omp parallel for
   for (int i = 0; i < m; ++i)
     for (int j = 0; j < n; ++j) {
-      double v = C[(size_t)i * n + j] + (double)bias[i];
-      C[(size_t)i * n + j] = v > 0.0 ? v : 0.0;
-      S[(size_t)i * n + j] += fabs((double)bias[i]);
+      double b = bias ? (double)bias[i] : 0.0;      /* no bias given: the epilogue adds nothing */
+      double v = C[(size_t)i * n + j] + b;
+      C[(size_t)i * n + j] = (relu && !(v > 0.0)) ? 0.0 : v;
+      S[(size_t)i * n + j] += fabs(b);
     }
 }
 

@@ -19,6 +19,8 @@ EXPORTS = (
     "spdl_spmm", "spdl_sddmm", "spdl_spmm_f16", "spdl_sddmm_f16", "spdl_build_row_order",
     "spdl_validate_csr_host", "spdl_select_spmm", "spdl_select_sddmm", "spdl_force_variant",
     "spdl_variant_name", "spdl_status_string", "spdl_version",
+    "spdl_spmm_bias_relu", "spdl_spmm_bias_relu_f16", "spdl_csr_softmax", "spdl_build_transpose_host",
+    "spdl_permute_values",
 )
 
 
@@ -129,6 +131,50 @@ def spdl_sddmm_f16(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, 
     return out_values
 
 
+def spdl_spmm_bias_relu(m, k, n, nnz, row_offsets, column_indices, values, row_order, B, bias, relu, C,
+                        stream=None):
+    import torch
+    _check(lib().spdl_spmm_bias_relu(
+        int(m), int(k), int(n), int(nnz), _dev(row_offsets, torch.int32, "row_offsets"),
+        _dev(column_indices, torch.int32, "column_indices"), _dev(values, torch.float32, "values"),
+        _dev(row_order, torch.int32, "row_order", allow_none=True), _dev(B, torch.float32, "B"),
+        _dev(bias, torch.float32, "bias", allow_none=True), int(bool(relu)),
+        _dev(C, torch.float32, "C"), _stream(stream)), "spdl_spmm_bias_relu")
+    return C
+
+
+def spdl_spmm_bias_relu_f16(m, k, n, nnz, row_offsets, column_indices, values, row_order, B, bias, relu, C,
+                            stream=None):
+    import torch
+    _check(lib().spdl_spmm_bias_relu_f16(
+        int(m), int(k), int(n), int(nnz), _dev(row_offsets, torch.int32, "row_offsets"),
+        _dev(column_indices, torch.int32, "column_indices"), _dev(values, torch.float16, "values"),
+        _dev(row_order, torch.int32, "row_order", allow_none=True), _dev(B, torch.float16, "B"),
+        _dev(bias, torch.float16, "bias", allow_none=True), int(bool(relu)),
+        _dev(C, torch.float16, "C"), _stream(stream)), "spdl_spmm_bias_relu_f16")
+    return C
+
+
+def spdl_csr_softmax(m, nnz, row_offsets, logits, scale, probabilities, stream=None):
+    import torch
+    _check(lib().spdl_csr_softmax(
+        int(m), int(nnz), _dev(row_offsets, torch.int32, "row_offsets"),
+        _dev(logits, torch.float32, "logits"), ctypes.c_float(float(scale)),
+        _dev(probabilities, torch.float32, "probabilities"), _stream(stream)), "spdl_csr_softmax")
+    return probabilities
+
+
+def spdl_permute_values(nnz, elem_bytes, perm, values, out, stream=None):
+    import torch
+    dtype = {2: torch.float16, 4: torch.float32}.get(int(elem_bytes))
+    if dtype is None:
+        raise ValueError("elem_bytes must be 2 or 4")
+    _check(lib().spdl_permute_values(
+        int(nnz), int(elem_bytes), _dev(perm, torch.int32, "perm"), _dev(values, dtype, "values"),
+        _dev(out, dtype, "out"), _stream(stream)), "spdl_permute_values")
+    return out
+
+
 def _host_i32(a, name):
     a = np.ascontiguousarray(a)
     if a.dtype != np.int32:
@@ -156,6 +202,22 @@ def spdl_validate_csr_host(m, k, nnz, row_offsets_host, column_indices_host):
     st = lib().spdl_validate_csr_host(int(m), int(k), int(nnz), ro.ctypes.data_as(ctypes.c_void_p),
                                       ci.ctypes.data_as(ctypes.c_void_p), ctypes.byref(flag))
     return int(st), bool(flag.value)
+
+
+def spdl_build_transpose_host(m, k, nnz, row_offsets_host, column_indices_host):
+    """Returns (t_row_offsets, t_column_indices, perm) as numpy int32 arrays."""
+    ro = _host_i32(row_offsets_host, "row_offsets_host")
+    ci = _host_i32(column_indices_host, "column_indices_host")
+    if ro.shape[0] != m + 1 or ci.shape[0] != nnz:
+        raise ValueError("array lengths do not match m / nnz")
+    t_ro = np.empty(k + 1, dtype=np.int32)
+    t_ci = np.empty(nnz, dtype=np.int32)
+    perm = np.empty(nnz, dtype=np.int32)
+    _check(lib().spdl_build_transpose_host(
+        int(m), int(k), int(nnz), ro.ctypes.data_as(ctypes.c_void_p), ci.ctypes.data_as(ctypes.c_void_p),
+        t_ro.ctypes.data_as(ctypes.c_void_p), t_ci.ctypes.data_as(ctypes.c_void_p),
+        perm.ctypes.data_as(ctypes.c_void_p)), "spdl_build_transpose_host")
+    return t_ro, t_ci, perm
 
 
 def _ptr_or_zero(t):

@@ -77,4 +77,19 @@ template <> struct Pack<_Float16, 8> {
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Optional epilogue of SpMM (paper Sec. "Application: Sparse MobileNetV1": bias and ReLU fused
+// into the sparse 1x1 convolution): v + bias[row], then max(., 0).  bias == nullptr: none.
+template <typename T, int N>
+__device__ __forceinline__ void spmm_epilogue(float (&acc)[N], const T* __restrict__ bias, int row, int relu) {
+  if (bias) {
+    const float b = (float)bias[row];
+#pragma unroll
+    for (int v = 0; v < N; ++v) acc[v] += b;
+  }
+  if (relu) {
+#pragma unroll
+    for (int v = 0; v < N; ++v) acc[v] = fmaxf(acc[v], 0.f);
+  }
+}
+
 }  // namespace spdl

@@ -10,6 +10,7 @@
 
 #include "../../include/spdl.h"
 #include "common.hpp"
+#include "csr_softmax.hpp"
 #include "sddmm_group.hpp"
 #include "sddmm_rowstrip.hpp"
 #include "sddmm_slab.hpp"
@@ -127,13 +128,13 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
 
 template <typename T, int VEC>
 int launch_spmm_rowsplit_g(const spdl_launch_info& li, int m, int n, const int* ro, const int* ci,
-                           const T* val, const int* order, const T* B, T* C, hipStream_t st) {
+                           const T* val, const int* order, const T* B, T* C, const T* bias, int relu, hipStream_t st) {
   dim3 grid(li.grid_x, li.grid_y), block(256);
   switch (li.lanes_per_row) {
-    case 8: spmm_rowsplit_kernel<T, VEC, 8><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C); break;
-    case 16: spmm_rowsplit_kernel<T, VEC, 16><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C); break;
-    case 32: spmm_rowsplit_kernel<T, VEC, 32><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C); break;
-    case 64: spmm_rowsplit_kernel<T, VEC, 64><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C); break;
+    case 8: spmm_rowsplit_kernel<T, VEC, 8><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
+    case 16: spmm_rowsplit_kernel<T, VEC, 16><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
+    case 32: spmm_rowsplit_kernel<T, VEC, 32><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
+    case 64: spmm_rowsplit_kernel<T, VEC, 64><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
     default: return SPDL_ERR_INVALID;
   }
   return SPDL_OK;
@@ -141,13 +142,14 @@ int launch_spmm_rowsplit_g(const spdl_launch_info& li, int m, int n, const int* 
 
 template <typename T>
 int launch_spmm_rowsplit(const spdl_launch_info& li, int m, int n, const int* ro, const int* ci,
-                         const T* val, const int* order, const T* B, T* C, hipStream_t st) {
+                         const T* val, const int* order, const T* B, T* C, const T* bias, int relu,
+                         hipStream_t st) {
   switch (li.vec) {
-    case 1: return launch_spmm_rowsplit_g<T, 1>(li, m, n, ro, ci, val, order, B, C, st);
-    case 2: return launch_spmm_rowsplit_g<T, 2>(li, m, n, ro, ci, val, order, B, C, st);
-    case 4: return launch_spmm_rowsplit_g<T, 4>(li, m, n, ro, ci, val, order, B, C, st);
+    case 1: return launch_spmm_rowsplit_g<T, 1>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
+    case 2: return launch_spmm_rowsplit_g<T, 2>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
+    case 4: return launch_spmm_rowsplit_g<T, 4>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
     case 8:
-      if constexpr (sizeof(T) == 2) return launch_spmm_rowsplit_g<T, 8>(li, m, n, ro, ci, val, order, B, C, st);
+      if constexpr (sizeof(T) == 2) return launch_spmm_rowsplit_g<T, 8>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
       return SPDL_ERR_INVALID;
     default: return SPDL_ERR_INVALID;
   }
@@ -155,7 +157,7 @@ int launch_spmm_rowsplit(const spdl_launch_info& li, int m, int n, const int* ro
 
 template <typename T>
 int spmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const T* val,
-              const int* order, const T* B, T* C, void* stream) {
+              const int* order, const T* B, T* C, void* stream, const T* bias = nullptr, int relu = 0) {
   if (!sizes_ok(m, k, n, nnz)) return SPDL_ERR_INVALID;
   if (m == 0 || n == 0) return SPDL_OK;
   if (!ro || !C || (nnz > 0 && (!ci || !val || !B))) return SPDL_ERR_INVALID;
@@ -184,17 +186,19 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const 
       const int tiles = (n + kSlabTile - 1) / kSlabTile;
       const dim3 grid(li.grid_x), block(kSlabThreads);
       if (li.variant == kSpmmSlab) {
-        kernel<<<grid, block, kSlabLdsBytes, st>>>(m, k, n, nnz, tiles, li.grid_y, panels, ro, ci, val, order, B, C);
+        kernel<<<grid, block, kSlabLdsBytes, st>>>(m, k, n, nnz, tiles, li.grid_y, panels, ro, ci, val, order, B, C,
+                                                   bias, relu);
       } else {
         int tpw = li.grid_y;
-        void* args[] = {&m, &k, &n, &nnz, (void*)&tiles, &tpw, (void*)&panels, &ro, &ci, &val, &order, &B, &C};
+        void* args[] = {&m, &k, &n, &nnz, (void*)&tiles, &tpw, (void*)&panels, &ro, &ci, &val, &order, &B, &C,
+                        &bias, &relu};
         if (hipLaunchKernel(dma_kernel, grid, block, args, kSlabLdsBytes, st) != hipSuccess) return SPDL_ERR_LAUNCH;
       }
     } else {
       return SPDL_ERR_UNSUPPORTED;
     }
   } else {
-    rc = launch_spmm_rowsplit<T>(li, m, n, ro, ci, val, order, B, C, st);
+    rc = launch_spmm_rowsplit<T>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
   }
   if (rc != SPDL_OK) return rc;
   return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
@@ -363,6 +367,73 @@ int spdl_spmm_f16(int m, int k, int n, int nnz, const int* row_offsets, const in
                              reinterpret_cast<const _Float16*>(B), reinterpret_cast<_Float16*>(C), stream);
 }
 
+int spdl_spmm_bias_relu(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                        const float* values, const int* row_order, const float* B, const float* bias,
+                        int relu, float* C, void* stream) {
+  return spmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, values, row_order, B, C, stream, bias,
+                          relu != 0);
+}
+
+int spdl_spmm_bias_relu_f16(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                            const uint16_t* values, const int* row_order, const uint16_t* B,
+                            const uint16_t* bias, int relu, uint16_t* C, void* stream) {
+  return spmm_impl<_Float16>(m, k, n, nnz, row_offsets, column_indices,
+                             reinterpret_cast<const _Float16*>(values), row_order,
+                             reinterpret_cast<const _Float16*>(B), reinterpret_cast<_Float16*>(C), stream,
+                             reinterpret_cast<const _Float16*>(bias), relu != 0);
+}
+
+int spdl_csr_softmax(int m, int nnz, const int* row_offsets, const float* logits, float scale,
+                     float* probabilities, void* stream) {
+  if (m < 0 || nnz < 0) return SPDL_ERR_INVALID;
+  if (m == 0 || nnz == 0) return SPDL_OK;
+  if (!row_offsets || !logits || !probabilities) return SPDL_ERR_INVALID;
+  (void)hipGetLastError();
+  csr_softmax_kernel<<<dim3((m + 3) / 4), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
+      m, row_offsets, logits, scale, probabilities);
+  return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
+}
+
+int spdl_build_transpose_host(int m, int k, int nnz, const int* ro, const int* ci, int* t_ro, int* t_ci,
+                              int* perm) {
+  if (m < 0 || k < 0 || nnz < 0 || !ro || !t_ro || (nnz > 0 && (!ci || !t_ci || !perm))) return SPDL_ERR_INVALID;
+  if (ro[0] != 0 || ro[m] != nnz) return SPDL_ERR_BAD_CSR;
+  // counting sort by column; rows are visited in order, so equal columns keep the row order
+  std::fill(t_ro, t_ro + k + 1, 0);
+  for (int i = 0; i < m; ++i) {
+    if (ro[i + 1] < ro[i] || ro[i + 1] > nnz) return SPDL_ERR_BAD_CSR;
+    for (int p = ro[i]; p < ro[i + 1]; ++p) {
+      if (ci[p] < 0 || ci[p] >= k) return SPDL_ERR_BAD_CSR;
+      ++t_ro[ci[p] + 1];
+    }
+  }
+  for (int c = 0; c < k; ++c) t_ro[c + 1] += t_ro[c];
+  std::vector<int> cursor(t_ro, t_ro + k);
+  for (int i = 0; i < m; ++i)
+    for (int p = ro[i]; p < ro[i + 1]; ++p) {
+      const int t = cursor[ci[p]]++;
+      t_ci[t] = i;
+      perm[t] = p;
+    }
+  return SPDL_OK;
+}
+
+int spdl_permute_values(int nnz, int elem_bytes, const int* perm, const void* values, void* out, void* stream) {
+  if (nnz < 0 || (elem_bytes != 2 && elem_bytes != 4)) return SPDL_ERR_INVALID;
+  if (nnz == 0) return SPDL_OK;
+  if (!perm || !values || !out) return SPDL_ERR_INVALID;
+  (void)hipGetLastError();
+  const dim3 grid((nnz + 255) / 256), block(256);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (elem_bytes == 4)
+    permute_values_kernel<float><<<grid, block, 0, st>>>(nnz, perm, static_cast<const float*>(values),
+                                                         static_cast<float*>(out));
+  else
+    permute_values_kernel<uint16_t><<<grid, block, 0, st>>>(nnz, perm, static_cast<const uint16_t*>(values),
+                                                            static_cast<uint16_t*>(out));
+  return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
+}
+
 int spdl_sddmm(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                const float* L, const float* R, float* out_values, void* stream) {
   return sddmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stream);
@@ -442,6 +513,6 @@ const char* spdl_status_string(int status) {
   }
 }
 
-int spdl_version(void) { return 100; }
+int spdl_version(void) { return 110; }
 
 }  // extern "C"

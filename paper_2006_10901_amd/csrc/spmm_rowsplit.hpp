@@ -11,7 +11,7 @@ template <typename T, int VEC, int G>
 __global__ __launch_bounds__(256) void spmm_rowsplit_kernel(
     int m, int n, const int* __restrict__ row_offsets,
     const int* __restrict__ column_indices, const T* __restrict__ values, const int* __restrict__ row_order,
-    const T* __restrict__ B, T* __restrict__ C) {
+    const T* __restrict__ B, T* __restrict__ C, const T* __restrict__ bias, int relu) {
   constexpr int ROWS = 256 / G;
   constexpr int U = (G == kWave && VEC * sizeof(T) <= 16) ? 16 : 8;   // nonzeros in flight per lane
   const int sub = threadIdx.x / G;
@@ -56,6 +56,7 @@ __global__ __launch_bounds__(256) void spmm_rowsplit_kernel(
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = __builtin_fmaf(a, b[v], acc[v]);
   }
+  spmm_epilogue<T, VEC>(acc, bias, row, relu);
   if (active) Pack<T, VEC>::store(C + (size_t)row * n + col, acc);
 }
 

@@ -28,7 +28,7 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_dma_kernel(
     int m, int k, int n, int nnz, int tiles_n, int tiles_per_wg, int panels,
     const int* __restrict__ row_offsets, const int* __restrict__ column_indices,
     const float* __restrict__ values, const int* __restrict__ row_order, const float* __restrict__ B,
-    float* __restrict__ C) {
+    float* __restrict__ C, const float* __restrict__ bias, int relu) {
   using T = float;
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
   constexpr int kBufBytes = (S + 1) * kSlabTile * 4;      // S data rows + one all-zero row
@@ -200,7 +200,10 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_dma_kernel(
           for (int v = 0; v < 4; ++v) acc[j][v] = __builtin_fmaf(a, b[v], acc[j][v]);
         }
       }
-      if (rows[j].row >= 0 && col_ok) Pack<T, 4>::store(C + (size_t)rows[j].row * n + col, acc[j]);
+      if (rows[j].row >= 0 && col_ok) {
+        spmm_epilogue<T, 4>(acc[j], bias, rows[j].row, relu);
+        Pack<T, 4>::store(C + (size_t)rows[j].row * n + col, acc[j]);
+      }
     }
   }
 }

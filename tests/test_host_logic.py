@@ -69,6 +69,32 @@ def test_row_order_matches_oracle(spdl, oracle_lib):
     assert spdl.spdl_build_row_order(0, np.zeros(1, np.int32)).shape == (0,)
 
 
+def test_transpose_topology_matches_oracle_and_rejects_bad_input(spdl, oracle_lib):
+    for A in (wl.adversarial_csr(77, 90, 21), wl.adversarial_csr(60, 45, 22, sorted_cols=False),
+              wl.uniform_mask_csr(64, 200, 0.1, 23)):
+        got = spdl.spdl_build_transpose_host(A.m, A.k, A.nnz, A.row_offsets, A.column_indices)
+        ref = oracle_lib.transpose_topology(A.m, A.k, A.row_offsets, A.column_indices)
+        for a, b in zip(got, ref):
+            assert a.dtype == np.int32 and np.array_equal(a, b)
+    A = wl.adversarial_csr(40, 50, 24)
+    bad = A.column_indices.copy()
+    bad[3] = A.k
+    with pytest.raises(spdl.SpdlError) as e:
+        spdl.spdl_build_transpose_host(A.m, A.k, A.nnz, A.row_offsets, bad)
+    assert e.value.status == -3
+    lib = spdl.lib()
+    null, one = ctypes.c_void_p(0), ctypes.c_void_p(256)
+    assert lib.spdl_build_transpose_host(-1, 4, 0, one, one, one, one, one) == -1
+    assert lib.spdl_permute_values(5, 3, one, one, one, null) == -1
+    assert lib.spdl_permute_values(0, 4, null, null, null, null) == 0
+    assert lib.spdl_csr_softmax(4, 0, one, null, ctypes.c_float(1.0), null, null) == 0
+    assert lib.spdl_csr_softmax(4, 3, one, null, ctypes.c_float(1.0), one, null) == -1
+    assert lib.spdl_spmm_bias_relu(4, 4, 4, 3, null, one, one, null, one, one, 1, one, null) == -1
+    assert lib.spdl_spmm_bias_relu_f16(-4, 4, 4, 3, one, one, one, null, one, one, 1, one, null) == -1
+    e0 = spdl.spdl_build_transpose_host(0, 3, 0, np.zeros(1, np.int32), np.zeros(0, np.int32))
+    assert np.array_equal(e0[0], np.zeros(4, np.int32)) and e0[1].size == 0
+
+
 def test_validate_csr_host(spdl):
     A = wl.adversarial_csr(40, 50, 12)
     assert spdl.spdl_validate_csr_host(A.m, A.k, A.nnz, A.row_offsets, A.column_indices) == (0, True)

@@ -231,6 +231,12 @@ def test_spmm_bias_relu_against_dense(oracle_lib):
     assert np.allclose(S, S0 + np.abs(bias.astype(np.float64))[:, None], rtol=1e-13)
     zero_bias, _ = oracle_lib.spmm_bias_relu(30, 44, 13, A.row_offsets, A.column_indices, A.values, B, np.zeros(30, np.float32))
     assert np.array_equal(zero_bias, np.maximum(plain, 0.0))
+    # the two switches: without a bias nothing is added, without the activation negatives stay
+    none_relu, Sn = oracle_lib.spmm_bias_relu(30, 44, 13, A.row_offsets, A.column_indices, A.values, B, None)
+    assert np.array_equal(none_relu, np.maximum(plain, 0.0)) and np.array_equal(Sn, S0)
+    lin, _ = oracle_lib.spmm_bias_relu(30, 44, 13, A.row_offsets, A.column_indices, A.values, B, bias, relu=False)
+    assert np.allclose(lin, densify(A) @ B.astype(np.float64) + bias.astype(np.float64)[:, None], rtol=1e-12, atol=1e-12)
+    assert (lin < 0).any()
 
 
 def test_transpose_topology_and_transposed_spmm(oracle_lib):
