@@ -89,6 +89,61 @@ class Case:
         }
 
 
+class WidenedCase:
+    """An operation around the two kernels (softmax, fused epilogue, transposed SpMM): a launch
+    closure with its algorithmic bytes and, where it multiplies, useful flops."""
+
+    def __init__(self, name, op, kernel, nnz, launch, nbytes, flops=0.0):
+        self.name, self.op, self.kernel, self.nnz = name, op, kernel, nnz
+        self.launch, self.bytes, self.flops, self.ms = launch, nbytes, flops, []
+
+    report = Case.report
+
+
+def widened_cases(wl, spdl, torch):
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    out = []
+    # softmax of one attention head's scores (4096 x 4096 banded topology, 10 % dense)
+    A = wl.attention(0)["A"]
+    ro = dev(A.row_offsets)
+    x = torch.randn(A.nnz, device="cuda")
+    p = torch.empty_like(x)
+    out.append(WidenedCase("attention_head", "csr_softmax", "wave_per_row", A.nnz,
+                           lambda: spdl.spdl_csr_softmax(A.m, A.nnz, ro, x, 0.125, p),
+                           8 * A.nnz + 4 * (A.m + 1)))
+    # 1x1 convolution with bias and ReLU fused (fp16, 1024 x 1024 weights at 90 % sparsity, 56x56 pixels)
+    w = wl.conv1x1(False)
+    C1 = w["A"]
+    cro, cci, cval = dev(C1.row_offsets), dev(C1.column_indices), dev(C1.values)
+    corder = dev(spdl.spdl_build_row_order(C1.m, C1.row_offsets))
+    cB = dev(w["B"])
+    cbias = torch.randn(C1.m, device="cuda").half()
+    cC = torch.empty((C1.m, 3136), dtype=torch.float16, device="cuda")
+    info = spdl.spdl_select_spmm(C1.m, C1.k, 3136, C1.nnz, 2, cB, cC)
+    out.append(WidenedCase("conv1x1_f16", "spmm_bias_relu", spdl.spdl_variant_name(0, info["variant"]), C1.nnz,
+                           lambda: spdl.spdl_spmm_bias_relu_f16(C1.m, C1.k, 3136, C1.nnz, cro, cci, cval, corder, cB,
+                                                                cbias, 1, cC),
+                           spmm_bytes(C1.m, C1.k, 3136, C1.nnz, 2) + 2 * C1.m, 2.0 * C1.nnz * 3136))
+    # A^T B for the first Transformer feed-forward weight (the data gradient of that layer):
+    # cached transposed topology, values permuted on the device, then the ordinary SpMM
+    w = wl.transformer_ffn(1, with_dense=False)
+    F = w["A"]
+    tro_h, tci_h, perm_h = spdl.spdl_build_transpose_host(F.m, F.k, F.nnz, F.row_offsets, F.column_indices)
+    tro, tci, perm, fval = dev(tro_h), dev(tci_h), dev(perm_h), dev(F.values)
+    tval = torch.empty_like(fval)
+    torder = dev(spdl.spdl_build_row_order(F.k, tro_h))
+    tB = torch.randn((F.m, 4096), device="cuda")
+    tC = torch.empty((F.k, 4096), device="cuda")
+    info = spdl.spdl_select_spmm(F.k, F.m, 4096, F.nnz, 4, tB, tC)
+
+    def transposed():
+        spdl.spdl_permute_values(F.nnz, 4, perm, fval, tval)
+        spdl.spdl_spmm(F.k, F.m, 4096, F.nnz, tro, tci, tval, torder, tB, tC)
+    out.append(WidenedCase("ffn_W1_transposed", "permute+spmm", spdl.spdl_variant_name(0, info["variant"]), F.nnz,
+                           transposed, spmm_bytes(F.k, F.m, 4096, F.nnz) + 12 * F.nnz, 2.0 * F.nnz * 4096))
+    return out
+
+
 def time_cases(cases, steps, warmup, torch):
     """Warm up, then time `steps` passes over `cases`: wall clock around the whole region and a
     HIP event pair (on the launch stream) around every launch."""
@@ -224,6 +279,7 @@ def main():
             nm = "conv1x1_f16_skewed" if skew else "conv1x1_f16"
             extra.append(Case(nm, "spmm", w["A"], 3136, (w["B"],), spdl, torch, f16=True))
             extra.append(Case(nm, "sddmm", w["A"], 3136, (w["L"], w["R"]), spdl, torch, f16=True))
+        extra += widened_cases(wl, spdl, torch)
         time_cases(extra, max(5, args.steps // 2), 2, torch)
         result["other_configs"] = [c.report() for c in extra]
         ffn = [c for c in extra if c.name.startswith("ffn")]
