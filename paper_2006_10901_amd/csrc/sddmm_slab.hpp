@@ -89,7 +89,7 @@ __device__ __forceinline__ void sd_fetch(SdRow& r, int l16, int last_nz, const i
 template <int S>
 __device__ __forceinline__ int sd_scan(int c, int slab_start, int sub, unsigned& rel, int& cnt) {
   rel = (unsigned)(c - slab_start);
-  const unsigned long long mask = __ballot(rel < (unsigned)S);
+  const unsigned long long mask = __builtin_amdgcn_ballot_w64(rel < (unsigned)S);
   const unsigned lo = (unsigned)mask, hi = (unsigned)(mask >> 32);
   const int c0 = __builtin_ctz(~(lo & 0xffffu) | 0x10000u), c1 = __builtin_ctz(~(lo >> 16) | 0x10000u);
   const int c2 = __builtin_ctz(~(hi & 0xffffu) | 0x10000u), c3 = __builtin_ctz(~(hi >> 16) | 0x10000u);
@@ -153,12 +153,8 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_kernel(
 
   const int tid = threadIdx.x;
   // workgroup id -> (panel, column range); the ranges of one panel share an XCD
-  const int per_block = 8 * ksplit;
-  const int blk = blockIdx.x / per_block;
-  const int rem = blockIdx.x - blk * per_block;
-  const int panel = blk * 8 + (rem & 7);
-  if (panel >= panels) return;
-  const int kpart = rem >> 3;
+  int panel, kpart;
+  if (!slab_wg_map(blockIdx.x, panels, ksplit, panel, kpart)) return;
   const int k0 = kpart * slabs_per_part * S;
   const int k1 = min(k, k0 + slabs_per_part * S);
   const int nslabs = (k1 - k0 + S - 1) / S;

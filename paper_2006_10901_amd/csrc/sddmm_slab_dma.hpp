@@ -26,18 +26,14 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_dma_kernel(
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = uniform(tid >> 6);
   const int sub = lane >> 4;
   const int l16 = lane & 15;
   const int lane_b = l16 * 16;
   const int last_nz = nnz - 1;
 
-  const int per_block = 8 * ksplit;
-  const int blk = blockIdx.x / per_block;
-  const int rem = blockIdx.x - blk * per_block;
-  const int panel = blk * 8 + (rem & 7);
-  if (panel >= panels) return;
-  const int kpart = rem >> 3;
+  int panel, kpart;
+  if (!slab_wg_map(blockIdx.x, panels, ksplit, panel, kpart)) return;
   const int k0 = kpart * slabs_per_part * S;
   const int k1 = min(k, k0 + slabs_per_part * S);
   const int nslabs = (k1 - k0 + S - 1) / S;
@@ -49,21 +45,41 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_dma_kernel(
     *reinterpret_cast<float*>(lds_raw + (tid / CW) * kBufBytes + kZeroOff + (tid % CW) * 4) = 0.f;
 
   // Copy i of wave w fills slab rows (i*16 + w)*kRowsPerCopy .. ; lane L brings 16 bytes of row
-  // L / kLanesPerRow, and the hardware places lane L's bytes at base + 16*L.  Rows past k and
-  // columns past n are clamped into R: nothing valid ever reads them.
+  // L / kLanesPerRow, and the hardware places lane L's bytes at M0 + 16*L.  The address is a
+  // scalar base (start of the slab and column chunk in R, moved from stage to stage with scalar
+  // arithmetic) plus a per-lane byte offset that is the same in every stage except a ragged
+  // last slab, whose rows past k are clamped to row k-1, and a ragged last column chunk, whose
+  // columns past n are clamped to the chunk's first column: nothing valid ever reads those.
+  // (S * n * 4 < 2^31 is checked on the host.)
+  unsigned row_off[kCopies], row_off_last[kCopies];
+  const int last_rows = k - (k0 + (nslabs - 1) * S);        // rows of the last slab, 1..S
+#pragma unroll
+  for (int i = 0; i < kCopies; ++i) {
+    const int lrow = (i * 16 + wave) * kRowsPerCopy + lane / kLanesPerRow;
+    row_off[i] = (unsigned)lrow * (unsigned)n * 4u;
+    row_off_last[i] = (unsigned)min(lrow, last_rows - 1) * (unsigned)n * 4u;
+  }
+  // The copies are issued from inline assembly: the compiler treats its own direct-to-LDS loads
+  // as touching both memory paths and then turns every later wait, for LDS reads and for index
+  // loads alike, into a wait for everything.  Their completion is covered by the explicit full
+  // wait and barrier that end every stage.  M0 (the LDS destination) is not used by anything
+  // the compiler generates in this kernel.
   auto copy_stage = [&](int q) {
     q = min(q, last_stage);
     const int slab = q / ncc;
     const int cc = q - slab * ncc;
-    const int colg = cc * CW + (lane % kLanesPerRow) * 4;
-    const float* src = R + (colg < n ? colg : 0);
-    char* dst = lds_raw + (q & 1) * kBufBytes;
+    const int lcol = (lane % kLanesPerRow) * 4;
+    const unsigned col_off = cc * CW + lcol < n ? (unsigned)(lcol * 4) : 0u;
+    const char* base = reinterpret_cast<const char*>(R + (size_t)(k0 + slab * S) * n + cc * CW);
+    const unsigned dst = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)(lds_raw + (q & 1) * kBufBytes) +
+                         (unsigned)wave * 1024u;
+    const bool last = slab == nslabs - 1;
 #pragma unroll
     for (int i = 0; i < kCopies; ++i) {
-      const int lrow = (i * 16 + wave) * kRowsPerCopy;
-      const int r = min(k0 + slab * S + lrow + lane / kLanesPerRow, k - 1);
-      __builtin_amdgcn_global_load_lds(src + (size_t)r * n,
-                                       (__attribute__((address_space(3))) void*)(dst + lrow * ROWB), 16, 0, 0);
+      const unsigned voff = (last ? row_off_last[i] : row_off[i]) + col_off;
+      const unsigned m0v = dst + (unsigned)i * (16u * 1024u);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :: "s"(m0v), "v"(voff), "s"(base) : "memory");
     }
   };
 

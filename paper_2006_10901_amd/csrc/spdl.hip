@@ -71,7 +71,8 @@ void fill_spmm_rowsplit_info(int m, int n, const void* B, const void* C, spdl_la
 
 template <typename T>
 bool slab_usable(int n, int nnz, const void* B, const void* C) {
-  return n % 4 == 0 && nnz < (1 << 29) && aligned(B, 4 * sizeof(T)) && aligned(C, 4 * sizeof(T));
+  // 32-bit byte offsets: into the pair arrays, and from a slab's start to any of its elements
+  return n % 4 == 0 && n < (1 << 21) && nnz < (1 << 29) && aligned(B, 4 * sizeof(T)) && aligned(C, 4 * sizeof(T));
 }
 
 // One workgroup fits per CU (LDS), so a panel's tiles are split into just enough groups to
@@ -101,7 +102,7 @@ void fill_spmm_slab_info(int m, int n, int variant, spdl_launch_info* info) {
   info->lanes_per_row = 16;
   info->rows_per_block = rows;
   info->block_threads = kSlabThreads;
-  info->grid_x = ((panels + 7) / 8) * 8 * groups;
+  info->grid_x = slab_grid_size(panels, groups);
   info->grid_y = tpw;                       // tiles walked by one workgroup (the grid is 1-D)
 }
 
@@ -242,7 +243,8 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
     variant = !fast_ok ? kSddmmRowstrip
               : (sizeof(T) == 4 && reuse >= 2.0 && m >= 512 && fits && nnz < (1 << 29)) ? kSddmmSlabDma : kSddmmGroup;
   }
-  if ((variant == kSddmmSlab || variant == kSddmmSlabDma) && !(fast_ok && sizeof(T) == 4 && nnz < (1 << 29)))
+  if ((variant == kSddmmSlab || variant == kSddmmSlabDma) &&
+      !(fast_ok && sizeof(T) == 4 && nnz < (1 << 29) && n < (1 << 21)))   // 32-bit byte offsets
     variant = kSddmmGroup;
   if (variant == kSddmmGroup && !fast_ok) variant = kSddmmRowstrip;
   const int avg = m > 0 ? nnz / m : 0;
@@ -255,7 +257,7 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
     info->lanes_per_row = 16;
     info->rows_per_block = kSdRows;
     info->block_threads = kSdThreads;
-    info->grid_x = ((sh.panels + 7) / 8) * 8 * sh.ksplit;
+    info->grid_x = slab_grid_size(sh.panels, sh.ksplit);
     info->grid_y = sh.ksplit;               // column ranges of A (the grid is 1-D)
     return;
   }

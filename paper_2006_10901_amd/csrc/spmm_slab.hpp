@@ -122,6 +122,14 @@ __device__ __forceinline__ void slab_fetch(SlabRow& r, int l16, int last_nz, con
   r.a_next = in ? a : 0.f;
 }
 
+// Maximum of two wave-uniform values on the scalar unit (left to itself the compiler moves such
+// a maximum to the vector unit as soon as one of its uses is a vector select).
+__device__ __forceinline__ int scalar_max(int a, int b) {
+  int r;
+  asm("s_max_i32 %0, %1, %2" : "=s"(r) : "s"(a), "s"(b) : "scc");
+  return r;
+}
+
 // Number of leading set bits of a 16-bit piece of a wave mask (scalar arithmetic).
 __device__ __forceinline__ int leading16(unsigned piece) { return __builtin_ctz(~piece | 0x10000u); }
 
@@ -191,12 +199,9 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_kernel(
   // Workgroup id -> (panel, tile group): the tile groups of one row panel get ids that are
   // equal modulo 8, so they run on the same XCD and the panel's part of A stays in one L2.
   const int groups_n = (tiles_n + tiles_per_wg - 1) / tiles_per_wg;
-  const int per_block = 8 * groups_n;
-  const int blk = blockIdx.x / per_block;
-  const int rem = blockIdx.x - blk * per_block;
-  const int panel = blk * 8 + (rem & 7);
-  if (panel >= panels) return;
-  const int tile_begin = (rem >> 3) * tiles_per_wg;
+  int panel, tile_group;
+  if (!slab_wg_map(blockIdx.x, panels, groups_n, panel, tile_group)) return;
+  const int tile_begin = tile_group * tiles_per_wg;
   const int tile_end = min(tiles_n, tile_begin + tiles_per_wg);
   const int nslabs = (k + S - 1) / S;
   const int stages = (tile_end - tile_begin) * nslabs;

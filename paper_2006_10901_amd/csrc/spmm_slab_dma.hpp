@@ -37,18 +37,15 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_dma_kernel(
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = uniform(tid >> 6);
   const int sub = lane >> 4;
   const int l16 = lane & 15;
   const int lane_b = l16 * 16;
 
   const int groups_n = (tiles_n + tiles_per_wg - 1) / tiles_per_wg;
-  const int per_block = 8 * groups_n;
-  const int blk = blockIdx.x / per_block;
-  const int rem = blockIdx.x - blk * per_block;
-  const int panel = blk * 8 + (rem & 7);
-  if (panel >= panels) return;
-  const int tile_begin = (rem >> 3) * tiles_per_wg;
+  int panel, tile_group;
+  if (!slab_wg_map(blockIdx.x, panels, groups_n, panel, tile_group)) return;
+  const int tile_begin = tile_group * tiles_per_wg;
   const int tile_end = min(tiles_n, tile_begin + tiles_per_wg);
   const int nslabs = (k + S - 1) / S;
   const int stages = (tile_end - tile_begin) * nslabs;
@@ -57,21 +54,41 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_dma_kernel(
     *reinterpret_cast<float*>(lds_raw + (tid >> 6) * kBufBytes + kZeroOff + (tid & 63) * 4) = 0.f;
 
   // Slab copy: copy i of wave w fills slab rows (i*16 + w)*4 .. +3; lane L brings row L/16 of
-  // those, columns 4*(L%16) .. +3, and the hardware places lane L's 16 bytes at base + 16*L.
-  // Rows past k and columns past n are clamped into B: nothing valid ever reads them.
+  // those, columns 4*(L%16) .. +3, and the hardware places lane L's 16 bytes at M0 + 16*L.
+  // The address is a scalar base (start of the slab in B, moved from stage to stage with scalar
+  // arithmetic) plus a per-lane byte offset that is the same in every stage except a ragged
+  // last slab, whose rows past k are clamped to row k-1, and a ragged last tile, whose columns
+  // past n are clamped to the tile's first column: nothing valid ever reads those.
+  // (S * n * 4 < 2^31 is checked on the host.)
+  unsigned row_off[kCopies], row_off_last[kCopies];
+  const int last_rows = k - (nslabs - 1) * S;               // rows of the last slab, 1..S
+#pragma unroll
+  for (int i = 0; i < kCopies; ++i) {
+    const int lrow = (i * 16 + wave) * 4 + sub;
+    row_off[i] = (unsigned)lrow * (unsigned)n * 4u;
+    row_off_last[i] = (unsigned)min(lrow, last_rows - 1) * (unsigned)n * 4u;
+  }
+  // The copies are issued from inline assembly: the compiler treats its own direct-to-LDS loads
+  // as touching both memory paths and then turns every later wait, for LDS reads and for pair
+  // loads alike, into a wait for everything.  Their completion is covered by the explicit full
+  // wait and barrier that end every stage.  M0 (the LDS destination) is not used by anything
+  // the compiler generates in this kernel.
   auto copy_stage = [&](int q) {
-    const int tile = tile_begin + q / nslabs;
-    const int slab = q - (q / nslabs) * nslabs;
-    const int colg = tile * kSlabTile + l16 * 4;
-    const float* src = B + (colg < n ? colg : 0);
-    char* dst = lds_raw + (q & 1) * kBufBytes;
+    const int t = q / nslabs;
+    const int slab = q - t * nslabs;
+    const int tile = tile_begin + t;
+    const bool ragged_tile = tile * kSlabTile + l16 * 4 >= n;
+    const unsigned col_off = ragged_tile ? 0u : (unsigned)(l16 * 16);
+    const char* base = reinterpret_cast<const char*>(B + (size_t)slab * S * n + tile * kSlabTile);
+    const unsigned dst = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)(lds_raw + (q & 1) * kBufBytes) +
+                         (unsigned)wave * (4 * kSlabTile * 4);
+    const bool last = slab == nslabs - 1;
 #pragma unroll
     for (int i = 0; i < kCopies; ++i) {
-      const int lrow = (i * 16 + wave) * 4;
-      const int r = min(slab * S + lrow + sub, k - 1);
-      __builtin_amdgcn_global_load_lds(src + (size_t)r * n,
-                                       (__attribute__((address_space(3))) void*)(dst + lrow * (kSlabTile * 4)),
-                                       16, 0, 0);
+      const unsigned voff = (last ? row_off_last[i] : row_off[i]) + col_off;
+      const unsigned m0v = dst + (unsigned)i * (16 * 4 * kSlabTile * 4);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :: "s"(m0v), "v"(voff), "s"(base) : "memory");
     }
   };
 
@@ -125,27 +142,31 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_dma_kernel(
     const int idx = at[j] + l16;
     float av[NCH];
     int off[NCH], cmax[NCH];
-    int total = 0, prev_cnt = 16;
+    // Everything derived from wave masks is wave-uniform and stays in scalar registers: the
+    // mask of usable pairs, the four groups' counts of leading usable pairs (one byte each in
+    // `counts`), their maximum, and the groups that may go on to the next chunk.
+    unsigned long long gate = ~0ull;      // groups whose previous chunk was consumed completely
+    unsigned counts = 0;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-      // chunk i continues chunk i-1 only where that one was consumed completely
       const unsigned rel = (unsigned)(cc[j][i] - slab_start);
-      const bool in = prev_cnt == 16 && idx + 16 * i < rows[j].row_end && rel < (unsigned)S;
-      // everything derived from the wave mask is wave-uniform and stays in scalar registers
-      const unsigned long long mk = __ballot(in);
+      const unsigned long long mk = __builtin_amdgcn_ballot_w64(idx + 16 * i < rows[j].row_end) &
+                                    __builtin_amdgcn_ballot_w64(rel < (unsigned)S) & gate;
       const unsigned lo = (unsigned)mk, hi = (unsigned)(mk >> 32);
       const int c0 = leading16(lo & 0xffffu), c1 = leading16(lo >> 16);
       const int c2 = leading16(hi & 0xffffu), c3 = leading16(hi >> 16);
-      cmax[i] = max(max(c0, c1), max(c2, c3));
-      const unsigned packed = (unsigned)c0 | ((unsigned)c1 << 8) | ((unsigned)c2 << 16) | ((unsigned)c3 << 24);
-      prev_cnt = (int)((packed >> sub8) & 0xffu);
-      total += prev_cnt;
+      cmax[i] = scalar_max(scalar_max(c0, c1), scalar_max(c2, c3));
+      counts += (unsigned)c0 | ((unsigned)c1 << 8) | ((unsigned)c2 << 16) | ((unsigned)c3 << 24);
+      if (i + 1 < NCH)
+        gate = (c0 == 16 ? 0xffffull : 0ull) | (c1 == 16 ? 0xffffull << 16 : 0ull) |
+               (c2 == 16 ? 0xffffull << 32 : 0ull) | (c3 == 16 ? 0xffffull << 48 : 0ull);
       // a pair inside the slab is used even if it is not among the leading ones (rows that
       // are not ascending): the cursor then stops short of the row end and the row is redone
+      const bool in = __builtin_amdgcn_inverse_ballot_w64(mk);
       av[i] = in ? aa[j][i] : 0.f;
       off[i] = in ? (int)(rel * (kSlabTile * 4)) : kZeroOff;
     }
-    rows[j].p += total;
+    rows[j].p += (int)((counts >> sub8) & 0xffu);
     const bool more = cmax[NCH - 1] == 16;
     // the next pairs, first needed in the next stage (or in the next long round of this one)
     fetch_pairs(j, (restart && !more) ? rows[j].p_begin : rows[j].p);
