@@ -131,7 +131,8 @@ typedef struct {
   int variant;          /* kernel family id                                        */
   int vec;              /* elements per lane per memory instruction                */
   int lanes_per_row;    /* lanes cooperating on one output row / one dot product   */
-  int rows_per_block;   /* sparse rows (SpMM) or nonzero strips (SDDMM) per block  */
+  int rows_per_block;   /* SpMM: sparse rows per block.  SDDMM: waves per row, or for the   */
+                        /* group variant the CSR entries owned by one wave                */
   int block_threads;
   int grid_x, grid_y;
 } spdl_launch_info;

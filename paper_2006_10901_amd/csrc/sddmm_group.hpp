@@ -61,46 +61,94 @@ __device__ __forceinline__ void sddmm_strip_direct(int n, int q, int end, int l1
     const int col = col0 + 4 * l16;
     const bool ok = col < n;
     const int colc = ok ? col : 0;
+    const int lane_off = colc;
+    // All sixteen gathers are issued before the first multiply-add (the scheduling barrier keeps
+    // the compiler from interleaving them with the arithmetic, which it otherwise does whenever
+    // the surrounding control flow changes, leaving two loads in flight instead of sixteen).
+    float r[16][4];
+#define SPDL_R1(T0) \
+    Pack<T, 4>::load(R + (__builtin_amdgcn_update_dpp(0, roff, 0x150 + (T0), 0xf, 0xf, false) + lane_off), r[T0]);
+    SPDL_R1(0) SPDL_R1(1) SPDL_R1(2) SPDL_R1(3) SPDL_R1(4) SPDL_R1(5) SPDL_R1(6) SPDL_R1(7)
+    SPDL_R1(8) SPDL_R1(9) SPDL_R1(10) SPDL_R1(11) SPDL_R1(12) SPDL_R1(13) SPDL_R1(14) SPDL_R1(15)
+#undef SPDL_R1
     float l[4];
     Pack<T, 4>::load(Lrow + colc, l);
-    if (!ok) l[0] = l[1] = l[2] = l[3] = 0.f;
-    const int lane_off = colc;
-#define SPDL_R4(T0)                                                                             \
-  {                                                                                             \
-    float r[4][4];                                                                              \
-    Pack<T, 4>::load(R + (__builtin_amdgcn_update_dpp(0, roff, 0x150 + (T0), 0xf, 0xf, false) + lane_off), r[0]);     \
-    Pack<T, 4>::load(R + (__builtin_amdgcn_update_dpp(0, roff, 0x150 + (T0) + 1, 0xf, 0xf, false) + lane_off), r[1]); \
-    Pack<T, 4>::load(R + (__builtin_amdgcn_update_dpp(0, roff, 0x150 + (T0) + 2, 0xf, 0xf, false) + lane_off), r[2]); \
-    Pack<T, 4>::load(R + (__builtin_amdgcn_update_dpp(0, roff, 0x150 + (T0) + 3, 0xf, 0xf, false) + lane_off), r[3]); \
-    _Pragma("unroll") for (int u = 0; u < 4; ++u)                                               \
-      _Pragma("unroll") for (int v = 0; v < 4; ++v)                                             \
-        partial[(T0) + u] = __builtin_fmaf(l[v], r[u][v], partial[(T0) + u]);                   \
-  }
-    SPDL_R4(0) SPDL_R4(4) SPDL_R4(8) SPDL_R4(12)
-#undef SPDL_R4
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) l[v] = ok ? l[v] : 0.f;
+#pragma unroll
+    for (int t = 0; t < 16; ++t)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) partial[t] = __builtin_fmaf(l[v], r[t][v], partial[t]);
   }
   const float total = reduce16x16(partial, l16);
   if (cidx < end) out[cidx] = (T)total;
 }
 
+// Work is split by nonzeros, not by rows: every wave owns `per_wave` consecutive entries of
+// the CSR arrays (a multiple of 64), finds the row of its first entry with a binary search in
+// the row offsets, and walks on from there.  The walk is wave-uniform (scalar loads and
+// arithmetic): it cuts the range into strips of up to 16 entries that end at row ends and
+// deals them to the four 16-lane groups, four at a time, so consecutive strips of one row
+// share its L row in cache and short rows still keep all four groups busy.  Outputs are
+// independent, so rows shared by several waves need no reduction, and the load per wave is
+// the same whatever the row lengths are (the balance the paper gets for SpMM from the row
+// swizzle, Sec. "Row Swizzle Load Balancing", without needing a row order in the interface).
 template <typename T>
 __global__ __launch_bounds__(256) void sddmm_group_kernel(
-    int m, int n, int split, const int* __restrict__ row_offsets,
+    int m, int n, int nnz, int per_wave, const int* __restrict__ row_offsets,
     const int* __restrict__ column_indices, const T* __restrict__ L, const T* __restrict__ R,
     T* __restrict__ out) {
-  const int lane = threadIdx.x & 63;
-  const int sub = lane >> 4;
-  const int l16 = lane & 15;
+  const int l16 = threadIdx.x & 15;
+  const int sub = (threadIdx.x & 63) >> 4;
   const int wave = uniform(blockIdx.x * 4 + (threadIdx.x >> 6));
-  const int row = wave / split;
-  const int part = wave - row * split;
-  if (row >= m) return;
-  const int start = row_offsets[row];
-  const int end = row_offsets[row + 1];
-  const T* Lrow = L + (size_t)row * n;
-  // the four groups of a wave take strips part*4+sub, then every split*4-th one
-  for (int q0 = start + part * 64; q0 < end; q0 += split * 64)
-    sddmm_strip_direct<T>(n, q0 + sub * 16, end, l16, Lrow, column_indices, R, out);
+  const long long first = (long long)wave * per_wave;
+  if (first >= nnz) return;
+  int p = (int)first;
+  const int range_end = (int)min((long long)nnz, first + per_wave);
+  // Last row whose offset is <= p: the row of entry p (rows in between are empty).  A 64-way
+  // search, one probe per lane: three rounds of dependent loads for up to 2^18 rows.
+  const int lane = threadIdx.x & 63;
+  int lo = 0, hi = m;                          // invariant: row_offsets[lo] <= p < row_offsets[hi]
+  while (hi - lo > 1) {
+    const int step = (hi - lo + 63) >> 6;
+    const int probe = lo + (lane + 1) * step;
+    const bool le = probe < hi && row_offsets[min(probe, hi)] <= p;     // true for a prefix of the lanes
+    const int cnt = __builtin_popcountll(__builtin_amdgcn_ballot_w64(le));
+    lo += cnt * step;
+    hi = min(hi, lo + step);
+  }
+  int row = lo;
+  int row_end = row_offsets[row + 1];
+  while (p < range_end) {
+    int my_row = 0, my_q = 0, my_end = 0;
+    while (row_end <= p) {                     // p reached the end of this row: next non-empty row
+      ++row;
+      row_end = row_offsets[row + 1];
+    }
+    const int seg_end = min(row_end, range_end);
+    if (p + 64 <= seg_end) {                   // four full strips of the same row
+      my_row = row;
+      my_q = p + 16 * sub;
+      my_end = seg_end;
+      p += 64;
+    } else {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        if (p < range_end) {
+          while (row_end <= p) {
+            ++row;
+            row_end = row_offsets[row + 1];
+          }
+          const int e = min(row_end, range_end);
+          if (sub == g) { my_row = row; my_q = p; my_end = e; }
+          p = min(p + 16, e);
+        }
+      }
+    }
+    if (my_q < my_end)
+      sddmm_strip_direct<T>(n, my_q, my_end, l16, L + (size_t)my_row * n, column_indices, R, out);
+  }
 }
 
 }  // namespace spdl

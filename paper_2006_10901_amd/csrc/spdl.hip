@@ -261,18 +261,23 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
     info->grid_y = sh.ksplit;               // column ranges of A (the grid is 1-D)
     return;
   }
-  int split;
   if (variant == kSddmmGroup) {
-    split = std::max(1, std::min(16, avg / 128));          // waves sharing one sparse row
+    // entries per wave: four strips of 16 while the machine (32 waves on each CU) is not
+    // full, then as many as keep the grid at about one wave per slot
+    const int64_t slots = (int64_t)kComputeUnits * 32;
+    const int quads = (int)std::max<int64_t>(1, std::min<int64_t>(64, ((int64_t)nnz / 64 + slots - 1) / slots));
     info->vec = 4;
     info->lanes_per_row = 16;
-  } else {
-    int vec = pick_vec<T>(n, L, R, 16 / (int)sizeof(T));
-    while (vec > 1 && kWave * vec / 2 >= n) vec /= 2;     // do not idle lanes on short dot products
-    split = std::max(1, std::min(8, avg / (4 * kStrip)));
-    info->vec = vec;
-    info->lanes_per_row = kWave;
+    info->rows_per_block = quads * 64;                     // entries per wave
+    const int64_t waves = ((int64_t)nnz + quads * 64 - 1) / (quads * 64);
+    info->grid_x = (int)((waves + 3) / 4);
+    return;
   }
+  int vec = pick_vec<T>(n, L, R, 16 / (int)sizeof(T));
+  while (vec > 1 && kWave * vec / 2 >= n) vec /= 2;     // do not idle lanes on short dot products
+  const int split = std::max(1, std::min(8, avg / (4 * kStrip)));
+  info->vec = vec;
+  info->lanes_per_row = kWave;
   info->rows_per_block = split;
   const int64_t waves = (int64_t)m * split;
   info->grid_x = (int)((waves + 3) / 4);
@@ -334,7 +339,7 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
     }
   }
   if (li.variant == kSddmmGroup) {
-    sddmm_group_kernel<T><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out);
+    sddmm_group_kernel<T><<<grid, block, 0, st>>>(m, n, nnz, li.rows_per_block, ro, ci, L, R, out);
     return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
   }
   switch (li.vec) {
