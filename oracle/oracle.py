@@ -93,6 +93,22 @@ def sddmm(m, k, n, row_offsets, column_indices, L, R):
     return out, S
 
 
+def sddmm_scaled(m, k, n, row_offsets, column_indices, values, L, R):
+    """Paper Sec. 'Sampled Dense--Dense Matrix Multiplication Operation' (strict definition): the
+    sampled products times the stored values of the sparse matrix.  fp32 inputs."""
+    lib = _load()
+    ro, ci = _csr_args(row_offsets, column_indices)
+    nnz = ci.shape[0]
+    v = np.ascontiguousarray(values, dtype=np.float32)
+    l = np.ascontiguousarray(L, dtype=np.float32)
+    r = np.ascontiguousarray(R, dtype=np.float32)
+    assert v.shape == (nnz,) and l.shape == (m, n) and r.shape == (k, n)
+    out = np.empty(nnz, dtype=np.float64)
+    S = np.empty(nnz, dtype=np.float64)
+    lib.oracle_sddmm_scaled_f32(m, k, n, _p(ro), _p(ci), _p(v), _p(l), _p(r), _p(out), _p(S))
+    return out, S
+
+
 def row_order(m, row_offsets):
     """Paper Sec. 'Row Binning & Row Bundling Heuristics': rows by decreasing length, stable."""
     lib = _load()

@@ -119,6 +119,18 @@ void oracle_sddmm_f32(int m, int k, int n, const int32_t* row_offsets, const int
   }
 }
 
+/* General SDDMM (paper Sec. "Sampled Dense--Dense Matrix Multiplication Operation", the strict
+ * definition and its footnote): the sampled products scaled element-wise by the values of the
+ * sparse matrix, out[p] = values[p] * sum_j L[i,j] R[c_p,j].  S[p] = |values[p]| * sum |L R|. */
+void oracle_sddmm_scaled_f32(int m, int k, int n, const int32_t* row_offsets, const int32_t* column_indices,
+                             const float* values, const float* L, const float* R, double* out, double* S) {
+  oracle_sddmm_f32(m, k, n, row_offsets, column_indices, L, R, out, S);
+  for (int p = 0; p < row_offsets[m]; ++p) {
+    out[p] *= (double)values[p];
+    S[p] *= fabs((double)values[p]);
+  }
+}
+
 void oracle_sddmm_f16(int m, int k, int n, const int32_t* row_offsets, const int32_t* column_indices,
                       const uint16_t* L, const uint16_t* R, double* out, double* S) {
   (void)k;

@@ -251,3 +251,23 @@ def test_transpose_topology_and_transposed_spmm(oracle_lib):
     B = wl.dense(A.m, 9, 97)
     C, _ = oracle_lib.spmm(A.k, A.m, 9, tro, tci, T.values, B)
     assert np.allclose(C, D.T @ B.astype(np.float64), rtol=1e-12, atol=1e-12)
+
+
+def test_sddmm_scaled_against_dense_hadamard(oracle_lib):
+    A = wl.adversarial_csr(41, 57, 98, sorted_cols=False)
+    L, R = wl.dense(41, 19, 99), wl.dense(57, 19, 100)
+    out, S = oracle_lib.sddmm_scaled(A.m, A.k, 19, A.row_offsets, A.column_indices, A.values, L, R)
+    P = L.astype(np.float64) @ R.astype(np.float64).T
+    rows = np.repeat(np.arange(A.m), np.diff(A.row_offsets))
+    ref = A.values.astype(np.float64) * P[rows, A.column_indices]          # A (Hadamard) L R^T, entry by entry
+    assert np.allclose(out, ref, rtol=1e-12, atol=1e-12)
+    plain, S0 = oracle_lib.sddmm(A.m, A.k, 19, A.row_offsets, A.column_indices, L, R)
+    assert np.allclose(S, np.abs(A.values.astype(np.float64)) * S0, rtol=1e-13)
+    ones = oracle_lib.sddmm_scaled(A.m, A.k, 19, A.row_offsets, A.column_indices, np.ones(A.nnz, np.float32), L, R)[0]
+    assert np.array_equal(ones, plain)                                      # unit values: the unscaled operation
+    # the scaled SDDMM summed over each row against all-ones R rows equals SpMM of A with ... a
+    # rank-one check: L = u 1^T, R = w 1^T gives out[p] = a_p * n * u_i * w_c exactly representable here
+    u = np.arange(1, A.m + 1, dtype=np.float32)[:, None] * np.ones((1, 4), np.float32)
+    w = np.arange(1, A.k + 1, dtype=np.float32)[:, None] * np.ones((1, 4), np.float32)
+    small = oracle_lib.sddmm_scaled(A.m, A.k, 4, A.row_offsets, A.column_indices, A.values, u, w)[0]
+    assert np.allclose(small, A.values.astype(np.float64) * 4.0 * (rows + 1) * (A.column_indices + 1), rtol=1e-14)
