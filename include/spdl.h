@@ -57,6 +57,20 @@ int spdl_spmm(int m, int k, int n, int nnz, const int* row_offsets, const int* c
 int spdl_sddmm(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                const float* L, const float* R, float* out_values, void* stream);
 
+/* General SDDMM (same section: the strict definition, with the element-wise scaling by the sparse
+ * matrix that the deep-learning form leaves out; the footnote there prices it at one load and
+ * one multiply before the store):
+ *   out_values[p] = values[p] * sum_j L[i,j] * R[column_indices[p], j].
+ *   values : DEVICE [nnz], the stored values of A; must not be the array out_values (an entry may
+ *   be computed more than once when a row's indices are not ascending).  Everything else as
+ *   spdl_sddmm.  The dot product is formed as in spdl_sddmm and multiplied once, in fp32; the
+ *   fp16 version rounds to binary16 after the multiplication. */
+int spdl_sddmm_scaled(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                      const float* values, const float* L, const float* R, float* out_values, void* stream);
+int spdl_sddmm_scaled_f16(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                          const uint16_t* values, const uint16_t* L, const uint16_t* R, uint16_t* out_values,
+                          void* stream);
+
 /* Mixed precision (paper Sec. "Mixed Precision"): operands and results are IEEE binary16
  * (passed as uint16_t bit patterns), every product and sum is fp32, results are rounded to
  * binary16 once (round to nearest even).  Column indices stay int32. */

@@ -20,7 +20,7 @@ EXPORTS = (
     "spdl_validate_csr_host", "spdl_select_spmm", "spdl_select_sddmm", "spdl_force_variant",
     "spdl_variant_name", "spdl_status_string", "spdl_version",
     "spdl_spmm_bias_relu", "spdl_spmm_bias_relu_f16", "spdl_csr_softmax", "spdl_build_transpose_host",
-    "spdl_permute_values",
+    "spdl_permute_values", "spdl_sddmm_scaled", "spdl_sddmm_scaled_f16",
 )
 
 
@@ -108,6 +108,26 @@ def spdl_sddmm(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stre
         _dev(column_indices, torch.int32, "column_indices"), _dev(L, torch.float32, "L"),
         _dev(R, torch.float32, "R"), _dev(out_values, torch.float32, "out_values"), _stream(stream)),
         "spdl_sddmm")
+    return out_values
+
+
+def spdl_sddmm_scaled(m, k, n, nnz, row_offsets, column_indices, values, L, R, out_values, stream=None):
+    import torch
+    _check(lib().spdl_sddmm_scaled(
+        int(m), int(k), int(n), int(nnz), _dev(row_offsets, torch.int32, "row_offsets"),
+        _dev(column_indices, torch.int32, "column_indices"), _dev(values, torch.float32, "values"),
+        _dev(L, torch.float32, "L"), _dev(R, torch.float32, "R"),
+        _dev(out_values, torch.float32, "out_values"), _stream(stream)), "spdl_sddmm_scaled")
+    return out_values
+
+
+def spdl_sddmm_scaled_f16(m, k, n, nnz, row_offsets, column_indices, values, L, R, out_values, stream=None):
+    import torch
+    _check(lib().spdl_sddmm_scaled_f16(
+        int(m), int(k), int(n), int(nnz), _dev(row_offsets, torch.int32, "row_offsets"),
+        _dev(column_indices, torch.int32, "column_indices"), _dev(values, torch.float16, "values"),
+        _dev(L, torch.float16, "L"), _dev(R, torch.float16, "R"),
+        _dev(out_values, torch.float16, "out_values"), _stream(stream)), "spdl_sddmm_scaled_f16")
     return out_values
 
 

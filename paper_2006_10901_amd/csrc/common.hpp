@@ -109,6 +109,15 @@ __host__ __device__ __forceinline__ int slab_grid_size(int panels, int groups) {
   return ((panels + 7) / 8) * 8 * groups;
 }
 
+// Store of one SDDMM result: as it is, or times the sparse matrix's value at that position (the
+// strict definition of SDDMM, paper Sec. "Sampled Dense--Dense Matrix Multiplication
+// Operation"; one load and one multiply before the store).  scale == nullptr: unscaled.
+template <typename T>
+__device__ __forceinline__ void sddmm_store(T* __restrict__ out, const T* __restrict__ scale, int p, float total) {
+  if (scale) total *= (float)scale[p];
+  out[p] = (T)total;
+}
+
 // Optional epilogue of SpMM (paper Sec. "Application: Sparse MobileNetV1": bias and ReLU fused
 // into the sparse 1x1 convolution): v + bias[row], then max(., 0).  bias == nullptr: none.
 template <typename T, int N>

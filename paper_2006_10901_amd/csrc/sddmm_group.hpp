@@ -51,7 +51,8 @@ __device__ __forceinline__ float reduce16x16(float (&x)[16], int l16) {
 template <typename T>
 __device__ __forceinline__ void sddmm_strip_direct(int n, int q, int end, int l16, const T* __restrict__ Lrow,
                                                    const int* __restrict__ column_indices,
-                                                   const T* __restrict__ R, T* __restrict__ out) {
+                                                   const T* __restrict__ R, T* __restrict__ out,
+                                                   const T* __restrict__ scale = nullptr) {
   const int cidx = q + l16;
   const int roff = column_indices[min(cidx, end - 1)] * n;     // past the end: last entry again
   float partial[16];
@@ -82,7 +83,7 @@ __device__ __forceinline__ void sddmm_strip_direct(int n, int q, int end, int l1
       for (int v = 0; v < 4; ++v) partial[t] = __builtin_fmaf(l[v], r[t][v], partial[t]);
   }
   const float total = reduce16x16(partial, l16);
-  if (cidx < end) out[cidx] = (T)total;
+  if (cidx < end) sddmm_store<T>(out, scale, cidx, total);
 }
 
 // Work is split by nonzeros, not by rows: every wave owns `per_wave` consecutive entries of
@@ -98,7 +99,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void sddmm_group_kernel(
     int m, int n, int nnz, int per_wave, const int* __restrict__ row_offsets,
     const int* __restrict__ column_indices, const T* __restrict__ L, const T* __restrict__ R,
-    T* __restrict__ out) {
+    T* __restrict__ out, const T* __restrict__ scale) {
   const int l16 = threadIdx.x & 15;
   const int sub = (threadIdx.x & 63) >> 4;
   const int wave = uniform(blockIdx.x * 4 + (threadIdx.x >> 6));
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(256) void sddmm_group_kernel(
       }
     }
     if (my_q < my_end)
-      sddmm_strip_direct<T>(n, my_q, my_end, l16, L + (size_t)my_row * n, column_indices, R, out);
+      sddmm_strip_direct<T>(n, my_q, my_end, l16, L + (size_t)my_row * n, column_indices, R, out, scale);
   }
 }
 

@@ -33,7 +33,7 @@ template <typename T, int VEC>
 __global__ __launch_bounds__(256) void sddmm_rowstrip_kernel(
     int m, int n, int split, const int* __restrict__ row_offsets,
     const int* __restrict__ column_indices, const T* __restrict__ L, const T* __restrict__ R,
-    T* __restrict__ out) {
+    T* __restrict__ out, const T* __restrict__ scale) {
   const int lane = threadIdx.x % kWave;
   const int wave = uniform(blockIdx.x * 4 + threadIdx.x / kWave);
   const int row = wave / split;
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void sddmm_rowstrip_kernel(
       }
     }
     const float total = strip_reduce32(partial, lane);
-    if (lane < kStrip && s + e < end) out[s + e] = (T)total;
+    if (lane < kStrip && s + e < end) sddmm_store<T>(out, scale, s + e, total);
   }
 }
 

@@ -59,8 +59,9 @@ __device__ __forceinline__ int sd_lower_bound16(const int* __restrict__ ci, int 
 // registers do not count against the main loop.
 template <typename T>
 __device__ __attribute__((noinline)) void sd_strip_direct_call(int n, int q, int end, int l16, const T* Lrow,
-                                                               const int* column_indices, const T* R, T* out) {
-  sddmm_strip_direct<T>(n, q, end, l16, Lrow, column_indices, R, out);
+                                                               const int* column_indices, const T* R, T* out,
+                                                               const T* scale) {
+  sddmm_strip_direct<T>(n, q, end, l16, Lrow, column_indices, R, out, scale);
 }
 
 struct SdRow {
@@ -142,7 +143,7 @@ template <typename T, int U, int S, bool DEFERRED>
 __global__ __launch_bounds__(kSdThreads) void sddmm_slab_kernel(
     int m, int k, int n, int nnz, int ksplit, int slabs_per_part, int panels,
     const int* __restrict__ row_offsets, const int* __restrict__ column_indices,
-    const T* __restrict__ L, const T* __restrict__ R, T* __restrict__ out) {
+    const T* __restrict__ L, const T* __restrict__ R, T* __restrict__ out, const T* __restrict__ scale) {
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
   constexpr int CW = 64 * U;                    // columns per stage
   constexpr int ROWB = CW * 4;                  // bytes per R row in LDS
@@ -272,7 +273,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_kernel(
           for (int t = 0; t < 16; ++t) partial[t] = 0.f;
           sd_steps<U>(partial, l[j], buf, off, lane_b, cmax);
           const float total = reduce16x16(partial, l16);
-          if (l16 < cnt) out[p_old + l16] = (T)total;
+          if (l16 < cnt) sddmm_store<T>(out, scale, p_old + l16, total);
           if (cmax < 16) break;
         }
       }
@@ -323,7 +324,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_kernel(
         for (int h = 0; h < 2; ++h)
           if (cmax[j][h] > 0) {
             const float total = reduce16x16(partial[j][h], l16);
-            if (l16 < cnt[j][h]) out[p_old[j] + 16 * h + l16] = (T)total;
+            if (l16 < cnt[j][h]) sddmm_store<T>(out, scale, p_old[j] + 16 * h + l16, total);
           }
         // more than 32 nonzeros of this row in this slab: the rest by direct gathers
         int more = cmax[j][1];
@@ -333,7 +334,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_kernel(
           more = sd_scan<S>(r.c_next, slab_start, sub, rel, c2);
           if (more == 0) break;
           if (c2 > 0)
-            sd_strip_direct_call<T>(n, r.p, r.p + c2, l16, L + (size_t)max(r.row, 0) * n, column_indices, R, out);
+            sd_strip_direct_call<T>(n, r.p, r.p + c2, l16, L + (size_t)max(r.row, 0) * n, column_indices, R, out, scale);
           r.p += c2;
           sd_fetch<true>(r, l16, last_nz, column_indices);
         }
@@ -347,7 +348,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_kernel(
     const SdRow& r = rows[j];
     if (r.p != r.p_end && r.row >= 0)
       for (int t = r.p_start; t < r.p_end; t += 16)
-        sd_strip_direct_call<T>(n, t, r.p_end, l16, L + (size_t)r.row * n, column_indices, R, out);
+        sd_strip_direct_call<T>(n, t, r.p_end, l16, L + (size_t)r.row * n, column_indices, R, out, scale);
   }
 }
 

@@ -13,7 +13,8 @@ template <int U, int S, bool DEFERRED>
 __global__ __launch_bounds__(kSdThreads) void sddmm_slab_dma_kernel(
     int m, int k, int n, int nnz, int ksplit, int slabs_per_part, int panels,
     const int* __restrict__ row_offsets, const int* __restrict__ column_indices,
-    const float* __restrict__ L, const float* __restrict__ R, float* __restrict__ out) {
+    const float* __restrict__ L, const float* __restrict__ R, float* __restrict__ out,
+    const float* __restrict__ scale) {
   using T = float;
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
   constexpr int CW = 64 * U;                    // columns per stage
@@ -134,7 +135,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_dma_kernel(
         for (int t = 0; t < 16; ++t) partial[t] = 0.f;
         sd_steps<U>(partial, l, buf, off, lane_b, cmax);
         const float total = reduce16x16(partial, l16);
-        if (l16 < cnt) out[p_old + l16] = (T)total;
+        if (l16 < cnt) sddmm_store<T>(out, scale, p_old + l16, total);
         if (cmax < 16) break;
       }
       __builtin_amdgcn_s_waitcnt(0);
@@ -177,7 +178,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_dma_kernel(
       for (int h = 0; h < 2; ++h)
         if (cmax[h] > 0) {
           const float total = reduce16x16(partial[h], l16);
-          if (l16 < cnt[h]) out[p_old + 16 * h + l16] = (T)total;
+          if (l16 < cnt[h]) sddmm_store<T>(out, scale, p_old + 16 * h + l16, total);
         }
       // more than 32 nonzeros of this row in this slab: the rest by direct gathers
       int more = cmax[1];
@@ -185,7 +186,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_dma_kernel(
         int c2;
         more = sd_scan<S>(r.c_next, slab_start, sub, rel, c2);
         if (more == 0) break;
-        if (c2 > 0) sd_strip_direct_call<T>(n, r.p, r.p + c2, l16, Lrow, column_indices, R, out);
+        if (c2 > 0) sd_strip_direct_call<T>(n, r.p, r.p + c2, l16, Lrow, column_indices, R, out, scale);
         r.p += c2;
         sd_fetch<true>(r, l16, last_nz, column_indices);
       }
@@ -195,7 +196,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_dma_kernel(
   // A range whose cursor did not stop exactly at its end was not ascending: redo it directly.
   if (r.p != r.p_end && r.row >= 0)
     for (int t = r.p_start; t < r.p_end; t += 16)
-      sd_strip_direct_call<T>(n, t, r.p_end, l16, Lrow, column_indices, R, out);
+      sd_strip_direct_call<T>(n, t, r.p_end, l16, Lrow, column_indices, R, out, scale);
 }
 
 }  // namespace spdl

@@ -285,7 +285,7 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
 
 template <typename T, int U, int S, bool DEFERRED>
 int launch_sddmm_slab(const SddmmSlabShape& sh, int grid, int m, int k, int n, int nnz, const int* ro,
-                      const int* ci, const T* L, const T* R, T* out, hipStream_t st, bool dma) {
+                      const int* ci, const T* L, const T* R, T* out, const T* scale, hipStream_t st, bool dma) {
   static std::atomic<bool> configured{false};
   static std::atomic<bool> configured_dma{false};
   if (dma) {
@@ -297,7 +297,7 @@ int launch_sddmm_slab(const SddmmSlabShape& sh, int grid, int m, int k, int n, i
       configured_dma.store(true);
     }
     kernel<<<dim3(grid), dim3(kSdThreads), sh.lds_bytes, st>>>(m, k, n, nnz, sh.ksplit, sh.spp, sh.panels, ro, ci,
-                                                               L, R, out);
+                                                               L, R, out, scale);
     return SPDL_OK;
   }
   auto kernel = sddmm_slab_kernel<T, U, S, DEFERRED>;
@@ -308,13 +308,13 @@ int launch_sddmm_slab(const SddmmSlabShape& sh, int grid, int m, int k, int n, i
     configured.store(true);
   }
   kernel<<<dim3(grid), dim3(kSdThreads), sh.lds_bytes, st>>>(m, k, n, nnz, sh.ksplit, sh.spp, sh.panels, ro, ci,
-                                                             L, R, out);
+                                                             L, R, out, scale);
   return SPDL_OK;
 }
 
 template <typename T>
 int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const T* L, const T* R,
-               T* out, void* stream) {
+               T* out, void* stream, const T* scale = nullptr) {
   if (!sizes_ok(m, k, n, nnz)) return SPDL_ERR_INVALID;
   if (m == 0 || nnz == 0) return SPDL_OK;
   if (!ro || !ci || !out || (n > 0 && (!L || !R))) return SPDL_ERR_INVALID;
@@ -329,9 +329,9 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
       const SddmmSlabShape sh = sddmm_slab_shape(m, k, n);
       const bool dma = li.variant == kSddmmSlabDma;
       int rc;
-      if (sh.deferred) rc = launch_sddmm_slab<T, 1, 128, true>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, st, dma);
-      else if (sh.U == 1) rc = launch_sddmm_slab<T, 1, 256, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, st, dma);
-      else rc = launch_sddmm_slab<T, 2, 128, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, st, dma);
+      if (sh.deferred) rc = launch_sddmm_slab<T, 1, 128, true>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma);
+      else if (sh.U == 1) rc = launch_sddmm_slab<T, 1, 256, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma);
+      else rc = launch_sddmm_slab<T, 2, 128, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma);
       if (rc != SPDL_OK) return rc;
       return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
     } else {
@@ -339,16 +339,16 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
     }
   }
   if (li.variant == kSddmmGroup) {
-    sddmm_group_kernel<T><<<grid, block, 0, st>>>(m, n, nnz, li.rows_per_block, ro, ci, L, R, out);
+    sddmm_group_kernel<T><<<grid, block, 0, st>>>(m, n, nnz, li.rows_per_block, ro, ci, L, R, out, scale);
     return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
   }
   switch (li.vec) {
-    case 1: sddmm_rowstrip_kernel<T, 1><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out); break;
-    case 2: sddmm_rowstrip_kernel<T, 2><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out); break;
-    case 4: sddmm_rowstrip_kernel<T, 4><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out); break;
+    case 1: sddmm_rowstrip_kernel<T, 1><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out, scale); break;
+    case 2: sddmm_rowstrip_kernel<T, 2><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out, scale); break;
+    case 4: sddmm_rowstrip_kernel<T, 4><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out, scale); break;
     case 8:
       if constexpr (sizeof(T) == 2) {
-        sddmm_rowstrip_kernel<T, 8><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out);
+        sddmm_rowstrip_kernel<T, 8><<<grid, block, 0, st>>>(m, n, split, ro, ci, L, R, out, scale);
         break;
       }
       return SPDL_ERR_INVALID;
@@ -444,6 +444,22 @@ int spdl_permute_values(int nnz, int elem_bytes, const int* perm, const void* va
 int spdl_sddmm(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                const float* L, const float* R, float* out_values, void* stream) {
   return sddmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stream);
+}
+
+int spdl_sddmm_scaled(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                      const float* values, const float* L, const float* R, float* out_values, void* stream) {
+  if (nnz > 0 && (!values || values == out_values)) return SPDL_ERR_INVALID;
+  return sddmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stream, values);
+}
+
+int spdl_sddmm_scaled_f16(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                          const uint16_t* values, const uint16_t* L, const uint16_t* R, uint16_t* out_values,
+                          void* stream) {
+  if (nnz > 0 && (!values || values == out_values)) return SPDL_ERR_INVALID;
+  return sddmm_impl<_Float16>(m, k, n, nnz, row_offsets, column_indices,
+                              reinterpret_cast<const _Float16*>(L), reinterpret_cast<const _Float16*>(R),
+                              reinterpret_cast<_Float16*>(out_values), stream,
+                              reinterpret_cast<const _Float16*>(values));
 }
 
 int spdl_sddmm_f16(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,

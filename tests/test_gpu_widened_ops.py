@@ -223,3 +223,62 @@ def test_transposed_spmm(g, oracle_lib, case):
     T = wl.Csr(A.k, A.m, tro, tci, tval.cpu().numpy())
     got = g.gpu_spmm(T, B, n, oracle_lib.row_order(A.k, otro))
     g.assert_close(got, C, S, g.TOL_F32, f"transposed spmm {case}")
+
+
+# ------------------------------------------------------------------ general SDDMM (scaled by A's values)
+def gpu_sddmm_scaled(g, A, L, R, n):
+    import torch
+    import paper_2006_10901_amd as spdl
+    f16 = L.dtype == np.float16
+    d = g.DevCsr(A)
+    dL, dR = g.dev(L), g.dev(R)
+    out = torch.full((A.nnz,), float("nan"), dtype=dL.dtype, device="cuda")
+    fn = spdl.spdl_sddmm_scaled_f16 if f16 else spdl.spdl_sddmm_scaled
+    fn(A.m, A.k, n, A.nnz, d.ro, d.ci, d.val, dL, dR, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(d.val.cpu().numpy(), A.values)          # the values are an input only
+    return out.cpu().numpy()
+
+
+def sddmm_variants():
+    import paper_2006_10901_amd as spdl
+    out, v = [], 0
+    while spdl.spdl_variant_name(1, v) is not None:
+        out.append(v)
+        v += 1
+    return out
+
+
+@pytest.mark.parametrize("n", [4, 68, 128, 200])
+def test_sddmm_scaled_every_variant(g, oracle_lib, force, n):
+    import paper_2006_10901_amd as spdl
+    for sorted_cols in (True, False):
+        A = wl.adversarial_csr(203, 700, 2300 + n, sorted_cols=sorted_cols)
+        L, R = wl.dense(A.m, n, 2301 + n), wl.dense(A.k, n, 2302 + n)
+        ref, S = oracle_lib.sddmm_scaled(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, L, R)
+        for v in sddmm_variants():
+            force(1, v)
+            got = gpu_sddmm_scaled(g, A, L, R, n)
+            g.assert_close(got, ref, S, g.TOL_F32, f"scaled sddmm {spdl.spdl_variant_name(1, v)} n={n} sorted={sorted_cols}")
+        force(1, -1)
+
+
+def test_sddmm_scaled_full_size_and_fp16(g, oracle_lib):
+    import torch
+    import paper_2006_10901_amd as spdl
+    w = wl.lstm(90)
+    A, L, R, n = w["A"], w["L"], w["R"], w["n"]
+    assert spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"]) == "slabdma"
+    ref, S = oracle_lib.sddmm_scaled(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, L, R)
+    g.assert_close(gpu_sddmm_scaled(g, A, L, R, n), ref, S, g.TOL_F32, "lstm-90 scaled sddmm")
+    c = wl.conv1x1(True)
+    A, L, R, n = c["A"], c["L"], c["R"], c["n"]
+    # binary16 -> binary32 is exact, so the fp32 oracle on the widened inputs is the fp16 oracle
+    ref, S = oracle_lib.sddmm_scaled(A.m, A.k, n, A.row_offsets, A.column_indices, A.values.astype(np.float32),
+                                     L.astype(np.float32), R.astype(np.float32))
+    g.assert_close(gpu_sddmm_scaled(g, A, L, R, n), ref, S, g.TOL_F16, "conv skewed scaled sddmm f16")
+    # the values array may not double as the output
+    d = g.DevCsr(w["A"])
+    with pytest.raises(spdl.SpdlError):
+        spdl.spdl_sddmm_scaled(d.m, d.k, 128, d.nnz, d.ro, d.ci, d.val, g.dev(w["L"]), g.dev(w["R"]), d.val)
+    torch.cuda.synchronize()
