@@ -12,19 +12,21 @@
 #include "common.hpp"
 #include "csr_softmax.hpp"
 #include "sddmm_group.hpp"
+#include "sddmm_mfma.hpp"
 #include "sddmm_rowstrip.hpp"
 #include "sddmm_slab.hpp"
 #include "sddmm_slab_dma.hpp"
 #include "spmm_rowsplit.hpp"
 #include "spmm_slab.hpp"
+#include "spmm_mfma.hpp"
 #include "spmm_slab_dma.hpp"
 
 namespace {
 
 using namespace spdl;
 
-enum SpmmVariant { kSpmmRowsplit = 0, kSpmmSlab = 1, kSpmmSlabDma = 2, kSpmmVariants };
-enum SddmmVariant { kSddmmRowstrip = 0, kSddmmGroup = 1, kSddmmSlab = 2, kSddmmSlabDma = 3, kSddmmVariants };
+enum SpmmVariant { kSpmmRowsplit = 0, kSpmmSlab = 1, kSpmmSlabDma = 2, kSpmmMfma = 3, kSpmmVariants };
+enum SddmmVariant { kSddmmRowstrip = 0, kSddmmGroup = 1, kSddmmSlab = 2, kSddmmSlabDma = 3, kSddmmMfma = 4, kSddmmVariants };
 
 std::atomic<int> g_forced[2] = {{-1}, {-1}};
 
@@ -109,9 +111,30 @@ void fill_spmm_slab_info(int m, int n, int variant, spdl_launch_info* info) {
 // Kernel selection (paper Sec. "Experiments": tile and vector width from the problem shape).
 // The slab kernel re-reads each B row from LDS once per sparse row that uses it, so it pays
 // when a 64-row panel touches the same B row several times: 64 * density >= 2.
+constexpr int kSpmmMfmaWaves = 2;                 // 256-column tiles per workgroup of the MFMA kernel
+constexpr int kSpmmMfmaKParts = 2;                // waves per tile, splitting the contraction
+
+// The matrix-core kernels (fp16 only) do dense work on 32-row panels / 32x32 blocks: worth it
+// when at least one position in 32 is stored.
+inline bool mfma_dense_enough(int m, int k, int nnz) { return 32.0 * (double)nnz >= (double)m * (double)k; }
+
 template <typename T>
 void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, spdl_launch_info* info) {
   int variant = g_forced[0].load();
+  const bool mfma_ok = sizeof(T) == 2 && n % 8 == 0 && aligned(B, 16) && aligned(C, 16);
+  if (variant == kSpmmMfma && (!mfma_ok || nnz == 0)) variant = kSpmmRowsplit;   // nnz == 0: B may be null
+  if (variant < 0 && mfma_ok && mfma_dense_enough(m, k, nnz)) variant = kSpmmMfma;
+  if (variant == kSpmmMfma) {
+    const int tiles_n = (n + 255) / 256;
+    info->variant = kSpmmMfma;
+    info->vec = 8;
+    info->lanes_per_row = kWave;
+    info->rows_per_block = 32;
+    info->block_threads = 64 * kSpmmMfmaWaves * kSpmmMfmaKParts;
+    info->grid_x = ((m + 31) / 32) * ((tiles_n + kSpmmMfmaWaves - 1) / kSpmmMfmaWaves);
+    info->grid_y = tiles_n;                     // 256-column tiles (the grid is 1-D)
+    return;
+  }
   if (variant < 0) {
     const double reuse = (m > 0 && k > 0) ? 64.0 * (double)nnz / ((double)m * (double)k) : 0.0;
     // one workgroup per CU: below half a machine of 64x64 output tiles the row-splitting
@@ -167,7 +190,22 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const 
   fill_spmm_info<T>(m, k, n, nnz, B, C, &li);
   (void)hipGetLastError();
   int rc = SPDL_OK;
-  if (li.variant == kSpmmSlab || li.variant == kSpmmSlabDma) {
+  if (li.variant == kSpmmMfma) {
+    if constexpr (sizeof(T) == 2) {
+      static std::atomic<int> configured{0};
+      const int lds = spmm_mfma_lds_bytes(k, kSpmmMfmaWaves);
+      auto kernel = spmm_mfma_kernel<kSpmmMfmaWaves, kSpmmMfmaKParts>;
+      if (configured.load() < lds) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                spmm_mfma_lds_bytes(kMfmaChunk, kSpmmMfmaWaves)) != hipSuccess)
+          return SPDL_ERR_LAUNCH;
+        configured.store(spmm_mfma_lds_bytes(kMfmaChunk, kSpmmMfmaWaves));
+      }
+      kernel<<<dim3(li.grid_x), dim3(li.block_threads), lds, st>>>(m, k, n, li.grid_y, ro, ci, val, B, C, bias, relu);
+    } else {
+      return SPDL_ERR_UNSUPPORTED;
+    }
+  } else if (li.variant == kSpmmSlab || li.variant == kSpmmSlabDma) {
     if constexpr (sizeof(T) == 4) {
       static std::atomic<bool> configured{false};
       auto kernel = spmm_slab_kernel<T, kSlabS>;
@@ -236,6 +274,21 @@ template <typename T>
 void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R, spdl_launch_info* info) {
   const bool fast_ok = sddmm_group_usable<T>(n, L, R);
   int variant = g_forced[1].load();
+  const bool mfma_ok = sizeof(T) == 2 && n > 0 && n % 8 == 0 && aligned(L, 16) && aligned(R, 16) &&
+                       (int64_t)((m + 63) / 64) * ((k + 63) / 64) < ((int64_t)1 << 31);
+  if (variant == kSddmmMfma && !mfma_ok) variant = kSddmmGroup;
+  if (variant < 0 && mfma_ok && mfma_dense_enough(m, k, nnz)) variant = kSddmmMfma;
+  if (variant == kSddmmMfma) {
+    const int64_t tiles = (int64_t)((m + 63) / 64) * ((k + 63) / 64);
+    info->variant = kSddmmMfma;
+    info->vec = 8;
+    info->lanes_per_row = kWave;
+    info->rows_per_block = 64;
+    info->block_threads = 256;
+    info->grid_x = (int)tiles;
+    info->grid_y = (k + 63) / 64;               // 64-column blocks per panel (the grid is 1-D)
+    return;
+  }
   if (variant < 0) {
     const double reuse = (m > 0 && k > 0) ? 64.0 * (double)nnz / ((double)m * (double)k) : 0.0;
     // wide dot products keep at most 32 nonzeros per row and 128-column slab in registers
@@ -324,6 +377,22 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
   dim3 grid(li.grid_x), block(256);
   const int split = li.rows_per_block;
   (void)hipGetLastError();
+  if (li.variant == kSddmmMfma) {
+    if constexpr (sizeof(T) == 2) {
+      static std::atomic<bool> configured{false};
+      if (!configured.load()) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(sddmm_mfma_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSddmmMfmaLdsBytes) != hipSuccess)
+          return SPDL_ERR_LAUNCH;
+        configured.store(true);
+      }
+      sddmm_mfma_kernel<<<dim3(li.grid_x), dim3(256), kSddmmMfmaLdsBytes, st>>>(m, k, n, li.grid_y, ro, ci, L, R, out,
+                                                                                scale);
+      return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
+    } else {
+      return SPDL_ERR_UNSUPPORTED;
+    }
+  }
   if (li.variant == kSddmmSlab || li.variant == kSddmmSlabDma) {
     if constexpr (sizeof(T) == 4) {
       const SddmmSlabShape sh = sddmm_slab_shape(m, k, n);
@@ -518,8 +587,8 @@ int spdl_force_variant(int op, int variant) {
 }
 
 const char* spdl_variant_name(int op, int variant) {
-  static const char* const spmm[] = {"rowsplit", "slab", "slabdma"};
-  static const char* const sddmm[] = {"rowstrip", "group", "slab", "slabdma"};
+  static const char* const spmm[] = {"rowsplit", "slab", "slabdma", "mfma"};
+  static const char* const sddmm[] = {"rowstrip", "group", "slab", "slabdma", "mfma"};
   if (op == 0 && variant >= 0 && variant < kSpmmVariants) return spmm[variant];
   if (op == 1 && variant >= 0 && variant < kSddmmVariants) return sddmm[variant];
   return nullptr;

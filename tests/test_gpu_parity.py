@@ -248,6 +248,8 @@ def test_forced_spmm_variants_ragged(g, oracle_lib, force, n):
     order = oracle_lib.row_order(A.m, A.row_offsets)
     results = []
     for v in spmm_variants():
+        if spdl.spdl_variant_name(0, v) == "mfma":
+            continue                                      # fp16 only, see the mixed-precision tests
         force(0, v)
         assert spdl.spdl_select_spmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"] == v
         got = g.gpu_spmm(A, B, n, order)
@@ -290,6 +292,8 @@ def test_forced_sddmm_variants_ragged(g, oracle_lib, force, n):
         L, R = wl.dense(A.m, n, 952 + n), wl.dense(A.k, n, 953 + n)
         out, S = oracle_lib.sddmm(A.m, A.k, n, A.row_offsets, A.column_indices, L, R)
         for v in sddmm_variants():
+            if spdl.spdl_variant_name(1, v) == "mfma":
+                continue                                  # fp16 only, see the mixed-precision tests
             force(1, v)
             assert spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"] == v
             got = g.gpu_sddmm(A, L, R, n)
@@ -307,3 +311,47 @@ def test_forced_sddmm_variants_fp16_and_long_rows(g, oracle_lib, force):
             force(1, v)
             got = g.gpu_sddmm(A, L, R, n)
             g.assert_close(got, out, S, tol, f"sddmm variant {spdl.spdl_variant_name(1, v)} {dt.__name__}")
+
+
+# ------------------------------------------------------------------ matrix-core kernels (fp16)
+def _f16(A):
+    A.values = A.values.astype(np.float16)
+    return A
+
+
+@pytest.mark.parametrize("n", [8, 24, 136, 264, 520])
+def test_mfma_kernels_edge_cases(g, oracle_lib, force, n):
+    import paper_2006_10901_amd as spdl
+    dup = wl.adversarial_csr(150, 600, 1101, sorted_cols=False)
+    dup.column_indices[5:9] = dup.column_indices[5]                 # duplicates inside a row
+    cases = [wl.adversarial_csr(203, 700, 1100 + n),                # m % 32 != 0, k % 16 != 0, empty rows
+             dup,
+             wl.adversarial_csr(70, 2500, 1102 + n),                 # k spans three panel chunks
+             wl.uniform_mask_csr(64, 96, 0.5, 1103 + n)]
+    for A in cases:
+        A = _f16(A)
+        B = wl.dense(A.k, n, 1104 + n, np.float16)
+        L, R = wl.dense(A.m, n, 1105 + n, np.float16), wl.dense(A.k, n, 1106 + n, np.float16)
+        force(0, 3)
+        force(1, 4)
+        assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(A.m, A.k, n, A.nnz, 2, 0, 0)["variant"]) == "mfma"
+        assert spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, 2, 0, 0)["variant"]) == "mfma"
+        spmm_case(g, oracle_lib, A, B, n, g.TOL_F16, "sorted", f"mfma spmm n={n} m={A.m} k={A.k}")
+        sddmm_case(g, oracle_lib, A, L, R, n, g.TOL_F16, f"mfma sddmm n={n} m={A.m} k={A.k}")
+        # the direct-gather kernels on the same inputs (what n % 8 != 0 or a sparser matrix would run)
+        force(0, 0)
+        force(1, 1)
+        spmm_case(g, oracle_lib, A, B, n, g.TOL_F16, "sorted", f"rowsplit spmm f16 n={n}")
+        sddmm_case(g, oracle_lib, A, L, R, n, g.TOL_F16, f"group sddmm f16 n={n}")
+
+
+def test_mfma_kernels_are_the_default_for_moderately_sparse_fp16(g):
+    import paper_2006_10901_amd as spdl
+    assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(1024, 1024, 3136, 104000, 2, 0, 0)["variant"]) == "mfma"
+    assert spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(1024, 1024, 3136, 104000, 2, 0, 0)["variant"]) == "mfma"
+    # one stored position in a hundred: gathers are cheaper than dense blocks
+    assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(1024, 1024, 3136, 10400, 2, 0, 0)["variant"]) == "rowsplit"
+    assert spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(1024, 1024, 3136, 10400, 2, 0, 0)["variant"]) == "group"
+    # fp32 never takes them, n % 8 != 0 neither
+    assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(1024, 1024, 3136, 104000, 4, 0, 0)["variant"]) != "mfma"
+    assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(1024, 1024, 3132, 104000, 2, 0, 0)["variant"]) == "rowsplit"

@@ -282,3 +282,23 @@ def test_sddmm_scaled_full_size_and_fp16(g, oracle_lib):
     with pytest.raises(spdl.SpdlError):
         spdl.spdl_sddmm_scaled(d.m, d.k, 128, d.nnz, d.ro, d.ci, d.val, g.dev(w["L"]), g.dev(w["R"]), d.val)
     torch.cuda.synchronize()
+
+
+def test_epilogue_and_scaling_on_the_matrix_core_kernels(g, oracle_lib, force):
+    import paper_2006_10901_amd as spdl
+    A = wl.adversarial_csr(203, 700, 2400)
+    A.values = A.values.astype(np.float16)
+    n = 136
+    B = wl.dense(A.k, n, 2401, np.float16)
+    bias = np.random.default_rng(2402).standard_normal(A.m).astype(np.float16)
+    force(0, 3)
+    force(1, 4)
+    for b, relu in ((bias, True), (bias, False), (None, True)):
+        C, S = oracle_lib.spmm_bias_relu(A.m, A.k, n, A.row_offsets, A.column_indices, A.values.astype(np.float32),
+                                         B.astype(np.float32), None if b is None else b.astype(np.float32), relu)
+        got = gpu_spmm_epilogue(g, A, B, n, b, relu, None)
+        g.assert_close(got, C, S, g.TOL_F16, f"mfma spmm bias={b is not None} relu={relu}")
+    L, R = wl.dense(A.m, n, 2403, np.float16), wl.dense(A.k, n, 2404, np.float16)
+    ref, S = oracle_lib.sddmm_scaled(A.m, A.k, n, A.row_offsets, A.column_indices, A.values.astype(np.float32),
+                                     L.astype(np.float32), R.astype(np.float32))
+    g.assert_close(gpu_sddmm_scaled(g, A, L, R, n), ref, S, g.TOL_F16, "mfma scaled sddmm")

@@ -128,10 +128,14 @@ def test_selection_uses_widest_aligned_vector(spdl):
     assert spdl.spdl_variant_name(1, d["variant"]) == "slabdma" and d["grid_x"] >= 256 and d["grid_y"] == 2
     d = spdl.spdl_select_sddmm(8192, 10240, 130, 8 << 20, 4, 0, 0)           # n % 4 != 0: general kernel
     assert spdl.spdl_variant_name(1, d["variant"]) == "rowstrip" and d["block_threads"] == 256
-    d = spdl.spdl_select_sddmm(1024, 1024, 3136, 100000, 2, 0, 0)            # fp16: strip kernel
+    d = spdl.spdl_select_sddmm(1024, 1024, 3136, 20000, 2, 0, 0)             # sparse fp16: strip kernel
     # split by nonzeros: waves of 64 entries each, 4 waves per block
     assert spdl.spdl_variant_name(1, d["variant"]) == "group" and d["rows_per_block"] == 64
-    assert d["grid_x"] == (100000 + 255) // 256
+    assert d["grid_x"] == (20000 + 255) // 256
+    d = spdl.spdl_select_sddmm(1024, 1024, 3136, 100000, 2, 0, 0)            # one position in ten: dense blocks
+    assert spdl.spdl_variant_name(1, d["variant"]) == "mfma" and d["grid_x"] == 16 * 16
+    s = spdl.spdl_select_spmm(1024, 1024, 3136, 100000, 2, 0, 0)
+    assert spdl.spdl_variant_name(0, s["variant"]) == "mfma" and s["grid_x"] == 32 * 7 and s["block_threads"] == 256
     assert spdl.spdl_variant_name(0, 0) is not None and spdl.spdl_variant_name(0, 99) is None
 
 
