@@ -111,6 +111,14 @@ def widened_cases(wl, spdl, torch):
     out.append(WidenedCase("attention_head", "csr_softmax", "wave_per_row", A.nnz,
                            lambda: spdl.spdl_csr_softmax(A.m, A.nnz, ro, x, 0.125, p),
                            8 * A.nnz + 4 * (A.m + 1)))
+    # the same for the eight heads of a layer stacked into one CSR matrix (32768 rows)
+    ro8 = np.concatenate([[0]] + [A.row_offsets[1:].astype(np.int64) + h * A.nnz for h in range(8)]).astype(np.int32)
+    dro8 = dev(ro8)
+    x8 = torch.randn(8 * A.nnz, device="cuda")
+    p8 = torch.empty_like(x8)
+    out.append(WidenedCase("attention_8_heads", "csr_softmax", "wave_per_row", 8 * A.nnz,
+                           lambda: spdl.spdl_csr_softmax(8 * A.m, 8 * A.nnz, dro8, x8, 0.125, p8),
+                           8 * 8 * A.nnz + 4 * (8 * A.m + 1)))
     # 1x1 convolution with bias and ReLU fused (fp16, 1024 x 1024 weights at 90 % sparsity, 56x56 pixels)
     w = wl.conv1x1(False)
     C1 = w["A"]
