@@ -25,6 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 FP32_VECTOR_PEAK_TFLOPS = 157.3      # 256 CUs x 2.4 GHz x 256 flop/clk/CU (published)
+MFMA_F16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 
 
@@ -33,7 +34,7 @@ HBM_PEAK_GBS = 8000.0
 # scaled by the copy-kernel factors given there.  Counters cannot be read from inside this
 # process, so the figures are carried here and refreshed whenever the kernels change.
 MEASURED_HBM_TRAFFIC_BYTES = {
-    "spmm_slabdma": 159.9e6, "sddmm_slabdma": 175.7e6, "spmm_rowsplit": 84.6e6, "sddmm_group": 154.3e6,
+    "spmm_slabdma": 159.9e6, "sddmm_slabdma": 173.8e6, "spmm_rowsplit": 84.2e6, "sddmm_group": 267.7e6,
 }
 
 
@@ -80,7 +81,13 @@ class Case:
 
     def report(self):
         t = float(np.mean(self.ms)) * 1e-3
-        return {
+        extra = {}
+        if self.kernel == "mfma":
+            # the matrix-core kernels do the dense block products: report that rate as well
+            dense = 2.0 * self.m * self.k * self.n
+            extra = {"dense_equiv_tflops": round(dense / t / 1e12, 1),
+                     "frac_mfma_f16_peak": round(dense / t / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)}
+        return {**extra, 
             "case": self.name, "op": self.op, "kernel": self.kernel, "nnz": self.nnz,
             "us": round(t * 1e6, 2), "us_min": round(float(np.min(self.ms)) * 1e3, 2),
             "gflops": round(self.flops / t / 1e9, 1), "eff_GBs": round(self.bytes / t / 1e9, 1),
@@ -93,9 +100,10 @@ class WidenedCase:
     """An operation around the two kernels (softmax, fused epilogue, transposed SpMM): a launch
     closure with its algorithmic bytes and, where it multiplies, useful flops."""
 
-    def __init__(self, name, op, kernel, nnz, launch, nbytes, flops=0.0):
+    def __init__(self, name, op, kernel, nnz, launch, nbytes, flops=0.0, dims=(0, 0, 0)):
         self.name, self.op, self.kernel, self.nnz = name, op, kernel, nnz
         self.launch, self.bytes, self.flops, self.ms = launch, nbytes, flops, []
+        self.m, self.k, self.n = dims
 
     report = Case.report
 
@@ -131,7 +139,8 @@ def widened_cases(wl, spdl, torch):
     out.append(WidenedCase("conv1x1_f16", "spmm_bias_relu", spdl.spdl_variant_name(0, info["variant"]), C1.nnz,
                            lambda: spdl.spdl_spmm_bias_relu_f16(C1.m, C1.k, 3136, C1.nnz, cro, cci, cval, corder, cB,
                                                                 cbias, 1, cC),
-                           spmm_bytes(C1.m, C1.k, 3136, C1.nnz, 2) + 2 * C1.m, 2.0 * C1.nnz * 3136))
+                           spmm_bytes(C1.m, C1.k, 3136, C1.nnz, 2) + 2 * C1.m, 2.0 * C1.nnz * 3136,
+                           dims=(C1.m, C1.k, 3136)))
     # A^T B for the first Transformer feed-forward weight (the data gradient of that layer):
     # cached transposed topology, values permuted on the device, then the ordinary SpMM
     w = wl.transformer_ffn(1, with_dense=False)
