@@ -1,5 +1,7 @@
 /*
- * libspdl -- CSR SpMM and SDDMM for deep-learning sparsity on AMD gfx950 (MI355X).
+ * libspdl -- CSR SpMM and SDDMM for deep-learning sparsity on AMD gfx950 (MI355X), with the
+ * operations around them: fused bias + ReLU, softmax over CSR rows, transposed topology, value
+ * scaling.
  *
  * C ABI.  Every pointer is marked HOST or DEVICE.  The library never allocates, frees or
  * keeps a caller's pointer, and never writes an input array.  Kernels are enqueued on
