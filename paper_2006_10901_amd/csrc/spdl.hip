@@ -253,14 +253,14 @@ bool sddmm_group_usable(int n, const void* L, const void* R) {
 // workgroup.
 struct SddmmSlabShape { int U, S, deferred, ksplit, spp, panels, lds_bytes; };
 
-// Dot products of up to 128 columns are finished inside a slab (U = 1 or 2 chunks of 64
-// columns per LDS row, 64 KB slabs).  Longer ones stream 64-column chunks of 128-row slabs and
-// keep two strips per row and slab in registers.
+// U chunks of 64 columns per LDS row (1 for n <= 64, else 2), 64 KB slabs.  Dot products of up to
+// 128 columns are finished inside a slab; longer ones stream 128-column pieces of 128-row slabs
+// and keep two strips per row and slab in registers.
 SddmmSlabShape sddmm_slab_shape(int m, int k, int n) {
   SddmmSlabShape sh;
   sh.deferred = n > 128;
-  sh.U = (n <= 64 || sh.deferred) ? 1 : 2;
-  sh.S = sh.deferred ? 128 : 256 / sh.U;
+  sh.U = n <= 64 ? 1 : 2;
+  sh.S = 256 / sh.U;
   sh.panels = (m + kSdRows - 1) / kSdRows;
   const int total = std::max(1, (k + sh.S - 1) / sh.S);
   const int want = std::max(1, std::min(total, (kComputeUnits + sh.panels - 1) / sh.panels));
@@ -398,7 +398,7 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
       const SddmmSlabShape sh = sddmm_slab_shape(m, k, n);
       const bool dma = li.variant == kSddmmSlabDma;
       int rc;
-      if (sh.deferred) rc = launch_sddmm_slab<T, 1, 128, true>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma);
+      if (sh.deferred) rc = launch_sddmm_slab<T, 2, 128, true>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma);
       else if (sh.U == 1) rc = launch_sddmm_slab<T, 1, 256, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma);
       else rc = launch_sddmm_slab<T, 2, 128, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma);
       if (rc != SPDL_OK) return rc;
