@@ -101,20 +101,23 @@ __device__ __forceinline__ int sd_scan(int c, int slab_start, int sub, unsigned&
 
 #define SPDL_SD_ADDR(T) (__builtin_amdgcn_update_dpp(0, off, 0x150 + (T), 0xf, 0xf, false) + lane_b)
 
-// partial[T] += dot(l, row of R at the LDS offset broadcast from lane T)
+// partial[T] (+)= dot(l, row of R at the LDS offset broadcast from lane T); with FRESH the sum
+// starts from the first product instead of from a zero that would have to be written first
 #define SPDL_SD_STEP(T)                                                                        \
   {                                                                                            \
     const int addr = SPDL_SD_ADDR(T);                                                          \
     _Pragma("unroll") for (int u = 0; u < U; ++u) {                                            \
       const f32x4 b = *reinterpret_cast<const f32x4*>(buf + addr + u * 256);                   \
-      partial[T] = __builtin_fmaf(l[u][0], b.x, partial[T]);                                   \
+      partial[T] = (FRESH && u == 0) ? l[u][0] * b.x : __builtin_fmaf(l[u][0], b.x, partial[T]); \
       partial[T] = __builtin_fmaf(l[u][1], b.y, partial[T]);                                   \
       partial[T] = __builtin_fmaf(l[u][2], b.z, partial[T]);                                   \
       partial[T] = __builtin_fmaf(l[u][3], b.w, partial[T]);                                   \
     }                                                                                          \
   }
 
-template <int U>
+// The up to 16 steps of one strip, in groups of four.  FRESH: `partial` holds nothing yet; the
+// sums of the steps that are not run are set to zero (the reduction adds all sixteen).
+template <int U, bool FRESH = false>
 __device__ __forceinline__ void sd_steps(float (&partial)[16], const float (&l)[U][4], const char* buf,
                                          int off, int lane_b, int cmax) {
   // The empty asm statements pin each group's sums where they are computed: without them the
@@ -122,6 +125,8 @@ __device__ __forceinline__ void sd_steps(float (&partial)[16], const float (&l)[
   // alive until then, which spills.
 #define SPDL_SD_PIN(T0) \
   asm volatile("" : "+v"(partial[T0]), "+v"(partial[T0 + 1]), "+v"(partial[T0 + 2]), "+v"(partial[T0 + 3]));
+#define SPDL_SD_ZERO(T0) \
+  if (FRESH) { _Pragma("unroll") for (int z = (T0); z < 16; ++z) partial[z] = 0.f; }
   SPDL_SD_STEP(0) SPDL_SD_STEP(1) SPDL_SD_STEP(2) SPDL_SD_STEP(3)
   SPDL_SD_PIN(0)
   if (cmax > 4) {
@@ -133,9 +138,16 @@ __device__ __forceinline__ void sd_steps(float (&partial)[16], const float (&l)[
       if (cmax > 12) {
         SPDL_SD_STEP(12) SPDL_SD_STEP(13) SPDL_SD_STEP(14) SPDL_SD_STEP(15)
         SPDL_SD_PIN(12)
+      } else {
+        SPDL_SD_ZERO(12)
       }
+    } else {
+      SPDL_SD_ZERO(8)
     }
+  } else {
+    SPDL_SD_ZERO(4)
   }
+#undef SPDL_SD_ZERO
 #undef SPDL_SD_PIN
 }
 
@@ -269,9 +281,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_kernel(
           r.p += cnt;
           sd_fetch<false>(r, l16, last_nz, column_indices);
           float partial[16];
-#pragma unroll
-          for (int t = 0; t < 16; ++t) partial[t] = 0.f;
-          sd_steps<U>(partial, l[j], buf, off, lane_b, cmax);
+          sd_steps<U, true>(partial, l[j], buf, off, lane_b, cmax);
           const float total = reduce16x16(partial, l16);
           if (l16 < cnt) sddmm_store<T>(out, scale, p_old + l16, total);
           if (cmax < 16) break;

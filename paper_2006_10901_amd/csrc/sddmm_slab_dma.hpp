@@ -131,9 +131,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_dma_kernel(
         r.p += cnt;
         sd_fetch<false>(r, l16, last_nz, column_indices);
         float partial[16];
-#pragma unroll
-        for (int t = 0; t < 16; ++t) partial[t] = 0.f;
-        sd_steps<U>(partial, l, buf, off, lane_b, cmax);
+        sd_steps<U, true>(partial, l, buf, off, lane_b, cmax);
         const float total = reduce16x16(partial, l16);
         if (l16 < cnt) sddmm_store<T>(out, scale, p_old + l16, total);
         if (cmax < 16) break;
