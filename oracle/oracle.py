@@ -109,6 +109,20 @@ def sddmm_scaled(m, k, n, row_offsets, column_indices, values, L, R):
     return out, S
 
 
+def sddmm_nt(m, k, n, row_offsets, column_indices, L, Rn):
+    """Same section, footnote: SDDMM with the right-hand operand not transposed (Rn is n x k)."""
+    lib = _load()
+    ro, ci = _csr_args(row_offsets, column_indices)
+    nnz = ci.shape[0]
+    l = np.ascontiguousarray(L, dtype=np.float32)
+    r = np.ascontiguousarray(Rn, dtype=np.float32)
+    assert l.shape == (m, n) and r.shape == (n, k)
+    out = np.empty(nnz, dtype=np.float64)
+    S = np.empty(nnz, dtype=np.float64)
+    lib.oracle_sddmm_nt_f32(m, k, n, _p(ro), _p(ci), _p(l), _p(r), _p(out), _p(S))
+    return out, S
+
+
 def row_order(m, row_offsets):
     """Paper Sec. 'Row Binning & Row Bundling Heuristics': rows by decreasing length, stable."""
     lib = _load()

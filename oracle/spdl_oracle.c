@@ -131,6 +131,28 @@ void oracle_sddmm_scaled_f32(int m, int k, int n, const int32_t* row_offsets, co
   }
 }
 
+/* SDDMM with the right-hand operand not transposed (same section, footnote: the general form
+ * takes the dense product L Rn with Rn of shape n x k, row-major):
+ * out[p] = sum_j L[i,j] * Rn[j, c_p].  Not scaled by A's values. */
+void oracle_sddmm_nt_f32(int m, int k, int n, const int32_t* row_offsets, const int32_t* column_indices,
+                         const float* L, const float* Rn, double* out, double* S) {
+#pragma omp parallel for schedule(dynamic, 16)
+  for (int i = 0; i < m; ++i) {
+    const float* l = L + (size_t)i * n;
+    for (int p = row_offsets[i]; p < row_offsets[i + 1]; ++p) {
+      const int c = column_indices[p];
+      double acc = 0.0, sc = 0.0;
+      for (int j = 0; j < n; ++j) {
+        double prod = (double)l[j] * (double)Rn[(size_t)j * k + c];
+        acc += prod;
+        sc += fabs(prod);
+      }
+      out[p] = acc;
+      S[p] = sc;
+    }
+  }
+}
+
 void oracle_sddmm_f16(int m, int k, int n, const int32_t* row_offsets, const int32_t* column_indices,
                       const uint16_t* L, const uint16_t* R, double* out, double* S) {
   (void)k;

@@ -271,3 +271,16 @@ def test_sddmm_scaled_against_dense_hadamard(oracle_lib):
     w = np.arange(1, A.k + 1, dtype=np.float32)[:, None] * np.ones((1, 4), np.float32)
     small = oracle_lib.sddmm_scaled(A.m, A.k, 4, A.row_offsets, A.column_indices, A.values, u, w)[0]
     assert np.allclose(small, A.values.astype(np.float64) * 4.0 * (rows + 1) * (A.column_indices + 1), rtol=1e-14)
+
+
+def test_sddmm_nt_against_dense_product_and_transposed_form(oracle_lib):
+    A = wl.adversarial_csr(33, 47, 101, sorted_cols=False)
+    L, Rn = wl.dense(33, 21, 102), wl.dense(21, 47, 103)                   # Rn is n x k: not square with L
+    out, S = oracle_lib.sddmm_nt(A.m, A.k, 21, A.row_offsets, A.column_indices, L, Rn)
+    P = L.astype(np.float64) @ Rn.astype(np.float64)                        # plain dense product, no transpose
+    rows = np.repeat(np.arange(A.m), np.diff(A.row_offsets))
+    assert np.allclose(out, P[rows, A.column_indices], rtol=1e-12, atol=1e-12)
+    assert np.allclose(S, (np.abs(L).astype(np.float64) @ np.abs(Rn).astype(np.float64))[rows, A.column_indices], rtol=1e-12)
+    # the transposed form on the transposed operand is the same sum in the same order
+    t_out, t_S = oracle_lib.sddmm(A.m, A.k, 21, A.row_offsets, A.column_indices, L, np.ascontiguousarray(Rn.T))
+    assert np.array_equal(out, t_out) and np.array_equal(S, t_S)
