@@ -73,6 +73,17 @@ int spdl_sddmm_scaled_f16(int m, int k, int n, int nnz, const int* row_offsets, 
                           const uint16_t* values, const uint16_t* L, const uint16_t* R, uint16_t* out_values,
                           void* stream);
 
+/* SDDMM with the right-hand operand not transposed (same footnote: the general form multiplies
+ * L by an n x k matrix):
+ *   out_values[p] = sum_j L[i,j] * Rn[j, column_indices[p]]   (times values[p] when values != NULL).
+ *   Rn : DEVICE [n*k], row-major n x k.  values : DEVICE [nnz] or NULL; not the array out_values.
+ *   Everything else as spdl_sddmm; k*n < 2^31.  Any n and alignment. */
+int spdl_sddmm_nt(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                  const float* values, const float* L, const float* Rn, float* out_values, void* stream);
+int spdl_sddmm_nt_f16(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                      const uint16_t* values, const uint16_t* L, const uint16_t* Rn, uint16_t* out_values,
+                      void* stream);
+
 /* Mixed precision (paper Sec. "Mixed Precision"): operands and results are IEEE binary16
  * (passed as uint16_t bit patterns), every product and sum is fp32, results are rounded to
  * binary16 once (round to nearest even).  Column indices stay int32. */
@@ -81,6 +92,12 @@ int spdl_spmm_f16(int m, int k, int n, int nnz, const int* row_offsets, const in
                   void* stream);
 int spdl_sddmm_f16(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                    const uint16_t* L, const uint16_t* R, uint16_t* out_values, void* stream);
+/* The same section's 16-bit column indices (they halve the index traffic of the sparse matrix):
+ * spdl_spmm_f16 with column_indices : DEVICE int16[nnz], each in [0,k), k <= 32767 (larger k:
+ * SPDL_ERR_INVALID).  Row offsets stay int32. */
+int spdl_spmm_f16_i16(int m, int k, int n, int nnz, const int* row_offsets, const int16_t* column_indices,
+                      const uint16_t* values, const int* row_order, const uint16_t* B, uint16_t* C,
+                      void* stream);
 
 /* SpMM with a fused epilogue (paper Sec. "Application: Sparse MobileNetV1": bias and ReLU are
  * fused into the sparse 1x1 convolution, whose weights are the sparse matrix and whose rows

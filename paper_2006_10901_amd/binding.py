@@ -21,6 +21,7 @@ EXPORTS = (
     "spdl_variant_name", "spdl_status_string", "spdl_version",
     "spdl_spmm_bias_relu", "spdl_spmm_bias_relu_f16", "spdl_csr_softmax", "spdl_build_transpose_host",
     "spdl_permute_values", "spdl_sddmm_scaled", "spdl_sddmm_scaled_f16",
+    "spdl_sddmm_nt", "spdl_sddmm_nt_f16", "spdl_spmm_f16_i16",
 )
 
 
@@ -129,6 +130,38 @@ def spdl_sddmm_scaled_f16(m, k, n, nnz, row_offsets, column_indices, values, L, 
         _dev(L, torch.float16, "L"), _dev(R, torch.float16, "R"),
         _dev(out_values, torch.float16, "out_values"), _stream(stream)), "spdl_sddmm_scaled_f16")
     return out_values
+
+
+def spdl_sddmm_nt(m, k, n, nnz, row_offsets, column_indices, values, L, Rn, out_values, stream=None):
+    import torch
+    _check(lib().spdl_sddmm_nt(
+        int(m), int(k), int(n), int(nnz), _dev(row_offsets, torch.int32, "row_offsets"),
+        _dev(column_indices, torch.int32, "column_indices"),
+        _dev(values, torch.float32, "values", allow_none=True), _dev(L, torch.float32, "L"),
+        _dev(Rn, torch.float32, "Rn"), _dev(out_values, torch.float32, "out_values"), _stream(stream)),
+        "spdl_sddmm_nt")
+    return out_values
+
+
+def spdl_sddmm_nt_f16(m, k, n, nnz, row_offsets, column_indices, values, L, Rn, out_values, stream=None):
+    import torch
+    _check(lib().spdl_sddmm_nt_f16(
+        int(m), int(k), int(n), int(nnz), _dev(row_offsets, torch.int32, "row_offsets"),
+        _dev(column_indices, torch.int32, "column_indices"),
+        _dev(values, torch.float16, "values", allow_none=True), _dev(L, torch.float16, "L"),
+        _dev(Rn, torch.float16, "Rn"), _dev(out_values, torch.float16, "out_values"), _stream(stream)),
+        "spdl_sddmm_nt_f16")
+    return out_values
+
+
+def spdl_spmm_f16_i16(m, k, n, nnz, row_offsets, column_indices, values, row_order, B, C, stream=None):
+    import torch
+    _check(lib().spdl_spmm_f16_i16(
+        int(m), int(k), int(n), int(nnz), _dev(row_offsets, torch.int32, "row_offsets"),
+        _dev(column_indices, torch.int16, "column_indices"), _dev(values, torch.float16, "values"),
+        _dev(row_order, torch.int32, "row_order", allow_none=True), _dev(B, torch.float16, "B"),
+        _dev(C, torch.float16, "C"), _stream(stream)), "spdl_spmm_f16_i16")
+    return C
 
 
 def spdl_spmm_f16(m, k, n, nnz, row_offsets, column_indices, values, row_order, B, C, stream=None):

@@ -13,6 +13,7 @@
 #include "csr_softmax.hpp"
 #include "sddmm_group.hpp"
 #include "sddmm_mfma.hpp"
+#include "sddmm_nt.hpp"
 #include "sddmm_rowstrip.hpp"
 #include "sddmm_slab.hpp"
 #include "sddmm_slab_dma.hpp"
@@ -150,37 +151,37 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
   }
 }
 
-template <typename T, int VEC>
-int launch_spmm_rowsplit_g(const spdl_launch_info& li, int m, int n, const int* ro, const int* ci,
+template <typename T, int VEC, typename I>
+int launch_spmm_rowsplit_g(const spdl_launch_info& li, int m, int n, const int* ro, const I* ci,
                            const T* val, const int* order, const T* B, T* C, const T* bias, int relu, hipStream_t st) {
   dim3 grid(li.grid_x, li.grid_y), block(256);
   switch (li.lanes_per_row) {
-    case 8: spmm_rowsplit_kernel<T, VEC, 8><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
-    case 16: spmm_rowsplit_kernel<T, VEC, 16><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
-    case 32: spmm_rowsplit_kernel<T, VEC, 32><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
-    case 64: spmm_rowsplit_kernel<T, VEC, 64><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
+    case 8: spmm_rowsplit_kernel<T, VEC, 8, I><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
+    case 16: spmm_rowsplit_kernel<T, VEC, 16, I><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
+    case 32: spmm_rowsplit_kernel<T, VEC, 32, I><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
+    case 64: spmm_rowsplit_kernel<T, VEC, 64, I><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
     default: return SPDL_ERR_INVALID;
   }
   return SPDL_OK;
 }
 
-template <typename T>
-int launch_spmm_rowsplit(const spdl_launch_info& li, int m, int n, const int* ro, const int* ci,
+template <typename T, typename I>
+int launch_spmm_rowsplit(const spdl_launch_info& li, int m, int n, const int* ro, const I* ci,
                          const T* val, const int* order, const T* B, T* C, const T* bias, int relu,
                          hipStream_t st) {
   switch (li.vec) {
-    case 1: return launch_spmm_rowsplit_g<T, 1>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
-    case 2: return launch_spmm_rowsplit_g<T, 2>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
-    case 4: return launch_spmm_rowsplit_g<T, 4>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
+    case 1: return launch_spmm_rowsplit_g<T, 1, I>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
+    case 2: return launch_spmm_rowsplit_g<T, 2, I>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
+    case 4: return launch_spmm_rowsplit_g<T, 4, I>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
     case 8:
-      if constexpr (sizeof(T) == 2) return launch_spmm_rowsplit_g<T, 8>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
+      if constexpr (sizeof(T) == 2) return launch_spmm_rowsplit_g<T, 8, I>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
       return SPDL_ERR_INVALID;
     default: return SPDL_ERR_INVALID;
   }
 }
 
-template <typename T>
-int spmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const T* val,
+template <typename T, typename I = int>
+int spmm_impl(int m, int k, int n, int nnz, const int* ro, const I* ci, const T* val,
               const int* order, const T* B, T* C, void* stream, const T* bias = nullptr, int relu = 0) {
   if (!sizes_ok(m, k, n, nnz)) return SPDL_ERR_INVALID;
   if (m == 0 || n == 0) return SPDL_OK;
@@ -190,11 +191,12 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const 
   fill_spmm_info<T>(m, k, n, nnz, B, C, &li);
   (void)hipGetLastError();
   int rc = SPDL_OK;
+  constexpr bool kInt32 = sizeof(I) == 4;        // the slab kernels read 32-bit indices only
   if (li.variant == kSpmmMfma) {
     if constexpr (sizeof(T) == 2) {
       static std::atomic<int> configured{0};
       const int lds = spmm_mfma_lds_bytes(k, kSpmmMfmaWaves);
-      auto kernel = spmm_mfma_kernel<kSpmmMfmaWaves, kSpmmMfmaKParts>;
+      auto kernel = spmm_mfma_kernel<kSpmmMfmaWaves, kSpmmMfmaKParts, I>;
       if (configured.load() < lds) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 spmm_mfma_lds_bytes(kMfmaChunk, kSpmmMfmaWaves)) != hipSuccess)
@@ -206,7 +208,7 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const 
       return SPDL_ERR_UNSUPPORTED;
     }
   } else if (li.variant == kSpmmSlab || li.variant == kSpmmSlabDma) {
-    if constexpr (sizeof(T) == 4) {
+    if constexpr (sizeof(T) == 4 && kInt32) {
       static std::atomic<bool> configured{false};
       auto kernel = spmm_slab_kernel<T, kSlabS>;
       // 32 pairs fetched ahead per row.  Deeper look-ahead (4 or 6 chunks of 16) was measured
@@ -237,7 +239,7 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const 
       return SPDL_ERR_UNSUPPORTED;
     }
   } else {
-    rc = launch_spmm_rowsplit<T>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
+    rc = launch_spmm_rowsplit<T, I>(li, m, n, ro, ci, val, order, B, C, bias, relu, st);
   }
   if (rc != SPDL_OK) return rc;
   return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
@@ -426,6 +428,18 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
   return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
 }
 
+template <typename T>
+int sddmm_nt_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const T* values, const T* L,
+                  const T* Rn, T* out, void* stream) {
+  if (!sizes_ok(m, k, n, nnz)) return SPDL_ERR_INVALID;
+  if (m == 0 || nnz == 0) return SPDL_OK;
+  if (!ro || !ci || !out || values == out || (n > 0 && (!L || !Rn))) return SPDL_ERR_INVALID;
+  (void)hipGetLastError();
+  sddmm_nt_kernel<T><<<dim3((nnz + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
+      m, k, n, nnz, ro, ci, L, Rn, out, values);
+  return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
@@ -513,6 +527,29 @@ int spdl_permute_values(int nnz, int elem_bytes, const int* perm, const void* va
 int spdl_sddmm(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                const float* L, const float* R, float* out_values, void* stream) {
   return sddmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stream);
+}
+
+int spdl_sddmm_nt(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                  const float* values, const float* L, const float* Rn, float* out_values, void* stream) {
+  return sddmm_nt_impl<float>(m, k, n, nnz, row_offsets, column_indices, values, L, Rn, out_values, stream);
+}
+
+int spdl_sddmm_nt_f16(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                      const uint16_t* values, const uint16_t* L, const uint16_t* Rn, uint16_t* out_values,
+                      void* stream) {
+  return sddmm_nt_impl<_Float16>(m, k, n, nnz, row_offsets, column_indices,
+                                 reinterpret_cast<const _Float16*>(values), reinterpret_cast<const _Float16*>(L),
+                                 reinterpret_cast<const _Float16*>(Rn), reinterpret_cast<_Float16*>(out_values),
+                                 stream);
+}
+
+int spdl_spmm_f16_i16(int m, int k, int n, int nnz, const int* row_offsets, const int16_t* column_indices,
+                      const uint16_t* values, const int* row_order, const uint16_t* B, uint16_t* C,
+                      void* stream) {
+  if (k > 32767) return SPDL_ERR_INVALID;           // the indices must fit 16 signed bits
+  return spmm_impl<_Float16, int16_t>(m, k, n, nnz, row_offsets, column_indices,
+                                      reinterpret_cast<const _Float16*>(values), row_order,
+                                      reinterpret_cast<const _Float16*>(B), reinterpret_cast<_Float16*>(C), stream);
 }
 
 int spdl_sddmm_scaled(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,

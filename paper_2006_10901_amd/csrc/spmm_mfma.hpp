@@ -39,10 +39,10 @@ __host__ __device__ __forceinline__ int spmm_mfma_lds_bytes(int k, int waves) {
 // WAVES tiles of 256 columns per workgroup, and KP waves per tile that split the steps of the
 // contraction between them (more loads in flight per CU; their accumulators are added up
 // through LDS at the end).
-template <int WAVES, int KP>
+template <int WAVES, int KP, typename I = int>
 __global__ __launch_bounds__(64 * WAVES * KP) void spmm_mfma_kernel(
     int m, int k, int n, int tiles_n, const int* __restrict__ row_offsets,
-    const int* __restrict__ column_indices, const _Float16* __restrict__ values,
+    const I* __restrict__ column_indices, const _Float16* __restrict__ values,
     const _Float16* __restrict__ B, _Float16* __restrict__ C, const _Float16* __restrict__ bias, int relu) {
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
   constexpr int THREADS = 64 * WAVES * KP;
@@ -128,8 +128,8 @@ __global__ __launch_bounds__(64 * WAVES * KP) void spmm_mfma_kernel(
 #pragma unroll
         for (int u = 0; u < EB; ++u) {
           const int p = min(base + u * THREADS, pend - 1);
-          cidx[u] = column_indices[p];
-          prev[u] = column_indices[max(p - 1, pbeg)];
+          cidx[u] = (int)column_indices[p];
+          prev[u] = (int)column_indices[max(p - 1, pbeg)];
           a[u] = values[p];
         }
 #pragma unroll
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(64 * WAVES * KP) void spmm_mfma_kernel(
     for (int p = row_offsets[row]; p < row_offsets[row + 1]; ++p) {
       const float a = (float)values[p];
       float b[4];
-      Pack<_Float16, 4>::load(B + (size_t)column_indices[p] * n + (ok ? col4 : 0), b);
+      Pack<_Float16, 4>::load(B + (size_t)(int)column_indices[p] * n + (ok ? col4 : 0), b);
 #pragma unroll
       for (int j = 0; j < 4; ++j) v[j] = __builtin_fmaf(a, b[j], v[j]);
     }

@@ -7,10 +7,12 @@
 
 namespace spdl {
 
-template <typename T, int VEC, int G>
+// I is the type of the column indices (int32, or int16 in the mixed-precision form of paper Sec.
+// "Mixed Precision", which halves the index traffic).
+template <typename T, int VEC, int G, typename I = int>
 __global__ __launch_bounds__(256) void spmm_rowsplit_kernel(
     int m, int n, const int* __restrict__ row_offsets,
-    const int* __restrict__ column_indices, const T* __restrict__ values, const int* __restrict__ row_order,
+    const I* __restrict__ column_indices, const T* __restrict__ values, const int* __restrict__ row_order,
     const T* __restrict__ B, T* __restrict__ C, const T* __restrict__ bias, int relu) {
   constexpr int ROWS = 256 / G;
   constexpr int U = (G == kWave && VEC * sizeof(T) <= 16) ? 16 : 8;   // nonzeros in flight per lane
@@ -41,7 +43,7 @@ __global__ __launch_bounds__(256) void spmm_rowsplit_kernel(
     int c[U];
     float b[U][VEC];
 #pragma unroll
-    for (int u = 0; u < U; ++u) { a[u] = (float)values[p + u]; c[u] = column_indices[p + u]; }
+    for (int u = 0; u < U; ++u) { a[u] = (float)values[p + u]; c[u] = (int)column_indices[p + u]; }
 #pragma unroll
     for (int u = 0; u < U; ++u) Pack<T, VEC>::load(Bcol + (size_t)c[u] * n, b[u]);
 #pragma unroll
@@ -52,7 +54,7 @@ __global__ __launch_bounds__(256) void spmm_rowsplit_kernel(
   for (; p < end; ++p) {
     const float a = (float)values[p];
     float b[VEC];
-    Pack<T, VEC>::load(Bcol + (size_t)column_indices[p] * n, b);
+    Pack<T, VEC>::load(Bcol + (size_t)(int)column_indices[p] * n, b);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = __builtin_fmaf(a, b[v], acc[v]);
   }

@@ -302,3 +302,72 @@ def test_epilogue_and_scaling_on_the_matrix_core_kernels(g, oracle_lib, force):
     ref, S = oracle_lib.sddmm_scaled(A.m, A.k, n, A.row_offsets, A.column_indices, A.values.astype(np.float32),
                                      L.astype(np.float32), R.astype(np.float32))
     g.assert_close(gpu_sddmm_scaled(g, A, L, R, n), ref, S, g.TOL_F16, "mfma scaled sddmm")
+
+
+# ------------------------------------------------------------------ non-transposed right-hand operand
+@pytest.mark.parametrize("n", [1, 7, 64, 130])
+def test_sddmm_nt(g, oracle_lib, n):
+    import torch
+    import paper_2006_10901_amd as spdl
+    for sorted_cols in (True, False):
+        A = wl.adversarial_csr(203, 157, 2500 + n, sorted_cols=sorted_cols)
+        L, Rn = wl.dense(A.m, n, 2501 + n), wl.dense(n, A.k, 2502 + n)
+        ref, S = oracle_lib.sddmm_nt(A.m, A.k, n, A.row_offsets, A.column_indices, L, Rn)
+        d = g.DevCsr(A)
+        out = torch.full((A.nnz,), float("nan"), device="cuda")
+        spdl.spdl_sddmm_nt(A.m, A.k, n, A.nnz, d.ro, d.ci, None, g.dev(L), g.dev(Rn), out)
+        torch.cuda.synchronize()
+        g.assert_close(out.cpu().numpy(), ref, S, g.TOL_F32, f"sddmm nt n={n}")
+        # with the element-wise scaling: values[p] times the same sum
+        out.fill_(float("nan"))
+        spdl.spdl_sddmm_nt(A.m, A.k, n, A.nnz, d.ro, d.ci, d.val, g.dev(L), g.dev(Rn), out)
+        torch.cuda.synchronize()
+        v = A.values.astype(np.float64)
+        g.assert_close(out.cpu().numpy(), v * ref, np.abs(v) * S, g.TOL_F32, f"scaled sddmm nt n={n}")
+        # fp16 operands (exactly representable in fp32, so the fp32 oracle on the widened inputs applies)
+        Lh, Rh = L.astype(np.float16), Rn.astype(np.float16)
+        refh, Sh = oracle_lib.sddmm_nt(A.m, A.k, n, A.row_offsets, A.column_indices, Lh.astype(np.float32),
+                                       Rh.astype(np.float32))
+        outh = torch.full((A.nnz,), float("nan"), dtype=torch.float16, device="cuda")
+        spdl.spdl_sddmm_nt_f16(A.m, A.k, n, A.nnz, d.ro, d.ci, None, g.dev(Lh), g.dev(Rh), outh)
+        torch.cuda.synchronize()
+        g.assert_close(outh.cpu().numpy(), refh, Sh, g.TOL_F16, f"sddmm nt f16 n={n}")
+
+
+def test_sddmm_nt_attention_size_equals_transposed_form(g, oracle_lib):
+    # the attention scores of one head, computed from K^T (64 x 4096) instead of K
+    import torch
+    import paper_2006_10901_amd as spdl
+    w = wl.attention(0)
+    A, Q, K = w["A"], w["Q"], w["K"]
+    ref, S = oracle_lib.sddmm_nt(4096, 4096, 64, A.row_offsets, A.column_indices, Q, np.ascontiguousarray(K.T))
+    d = g.DevCsr(A)
+    out = torch.full((A.nnz,), float("nan"), device="cuda")
+    spdl.spdl_sddmm_nt(4096, 4096, 64, A.nnz, d.ro, d.ci, None, g.dev(Q), g.dev(np.ascontiguousarray(K.T)), out)
+    torch.cuda.synchronize()
+    g.assert_close(out.cpu().numpy(), ref, S, g.TOL_F32, "attention scores from K^T")
+
+
+# ------------------------------------------------------------------ 16-bit column indices
+@pytest.mark.parametrize("n", [8, 50, 136])
+def test_spmm_f16_with_int16_indices(g, oracle_lib, force, n):
+    import torch
+    import paper_2006_10901_amd as spdl
+    dup = wl.adversarial_csr(150, 600, 2601, sorted_cols=False)
+    dup.column_indices[5:9] = dup.column_indices[5]
+    for A in (wl.adversarial_csr(203, 700, 2600 + n), dup, wl.adversarial_csr(70, 2500, 2602 + n)):
+        A.values = A.values.astype(np.float16)
+        B = wl.dense(A.k, n, 2603 + n, np.float16)
+        C, S = oracle_lib.spmm(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, B)
+        d = g.DevCsr(A)
+        ci16 = g.dev(A.column_indices.astype(np.int16))
+        order = g.dev(oracle_lib.row_order(A.m, A.row_offsets))
+        for variant in (-1, 0, 3):                      # the heuristic's choice, row splitting, matrix cores
+            force(0, variant)
+            got = torch.full((A.m, n), float("nan"), dtype=torch.float16, device="cuda")
+            spdl.spdl_spmm_f16_i16(A.m, A.k, n, A.nnz, d.ro, ci16, d.val, order, g.dev(B), got)
+            torch.cuda.synchronize()
+            g.assert_close(got.cpu().numpy(), C, S, g.TOL_F16, f"int16 indices n={n} variant={variant}")
+        force(0, -1)
+    with pytest.raises(spdl.SpdlError):                 # k does not fit 16 signed bits
+        spdl.spdl_spmm_f16_i16(4, 40000, 8, 0, d.ro, ci16, d.val, None, g.dev(B), got)

@@ -92,6 +92,11 @@ def test_transpose_topology_matches_oracle_and_rejects_bad_input(spdl, oracle_li
     assert lib.spdl_sddmm_scaled(4, 4, 4, 3, one, one, null, one, one, one, null) == -1
     assert lib.spdl_sddmm_scaled(4, 4, 4, 3, one, one, one, one, one, one, null) == -1        # values is out
     assert lib.spdl_sddmm_scaled_f16(4, 4, 4, 0, one, null, null, one, one, null, null) == 0
+    assert lib.spdl_sddmm_nt(4, 4, 4, 3, one, one, null, null, one, one, null) == -1
+    assert lib.spdl_sddmm_nt(4, 4, 4, 3, one, one, one, one, one, one, null) == -1            # values is out
+    assert lib.spdl_sddmm_nt_f16(4, 4, 4, 0, one, null, null, one, one, null, null) == 0
+    assert lib.spdl_spmm_f16_i16(4, 32768, 4, 3, one, one, one, null, one, one, null) == -1
+    assert lib.spdl_spmm_f16_i16(0, 4, 4, 0, null, null, null, null, null, null, null) == 0
     assert lib.spdl_spmm_bias_relu(4, 4, 4, 3, null, one, one, null, one, one, 1, one, null) == -1
     assert lib.spdl_spmm_bias_relu_f16(-4, 4, 4, 3, one, one, one, null, one, one, 1, one, null) == -1
     e0 = spdl.spdl_build_transpose_host(0, 3, 0, np.zeros(1, np.int32), np.zeros(0, np.int32))
