@@ -59,14 +59,26 @@ constexpr int kSlabS = 256;                       // B rows per LDS slab
 constexpr int kSlabLdsBytes = 2 * (kSlabS + 1) * kSlabTile * 4;
 constexpr int kComputeUnits = 256;
 
+// Lane groups per row of the row-splitting kernel: one, unless the rows are too few to fill the
+// machine (about 16 waves per CU) and long enough to share; only with the widest vectors.
 template <typename T>
-void fill_spmm_rowsplit_info(int m, int n, const void* B, const void* C, spdl_launch_info* info) {
+int pick_segments(int m, int nnz, int vec, int g) {
+  if (vec != 16 / (int)sizeof(T) || m <= 0) return 1;
+  int seg = 1;
+  const int64_t avg = nnz / m;
+  while (g * seg * 2 <= kWave && (int64_t)m * g * seg / kWave < 16 * kComputeUnits && avg / (seg * 2) >= 32) seg *= 2;
+  return seg;
+}
+
+template <typename T>
+void fill_spmm_rowsplit_info(int m, int n, int nnz, const void* B, const void* C, spdl_launch_info* info) {
   const int vec = pick_vec<T>(n, B, C, 16 / (int)sizeof(T));
   const int g = pick_group(n, vec);
+  const int seg = pick_segments<T>(m, nnz, vec, g);
   info->variant = kSpmmRowsplit;
   info->vec = vec;
   info->lanes_per_row = g;
-  info->rows_per_block = 256 / g;
+  info->rows_per_block = 256 / (g * seg);
   info->block_threads = 256;
   info->grid_x = (m + info->rows_per_block - 1) / info->rows_per_block;
   info->grid_y = (n + g * vec - 1) / (g * vec);
@@ -147,7 +159,7 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
   if ((variant == kSpmmSlab || variant == kSpmmSlabDma) && sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C)) {
     fill_spmm_slab_info(m, n, variant, info);
   } else {
-    fill_spmm_rowsplit_info<T>(m, n, B, C, info);
+    fill_spmm_rowsplit_info<T>(m, n, nnz, B, C, info);
   }
 }
 
@@ -155,14 +167,29 @@ template <typename T, int VEC, typename I>
 int launch_spmm_rowsplit_g(const spdl_launch_info& li, int m, int n, const int* ro, const I* ci,
                            const T* val, const int* order, const T* B, T* C, const T* bias, int relu, hipStream_t st) {
   dim3 grid(li.grid_x, li.grid_y), block(256);
-  switch (li.lanes_per_row) {
-    case 8: spmm_rowsplit_kernel<T, VEC, 8, I><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
-    case 16: spmm_rowsplit_kernel<T, VEC, 16, I><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
-    case 32: spmm_rowsplit_kernel<T, VEC, 32, I><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
-    case 64: spmm_rowsplit_kernel<T, VEC, 64, I><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); break;
-    default: return SPDL_ERR_INVALID;
-  }
+  const int seg = 256 / (li.rows_per_block * li.lanes_per_row);       // lane groups per row
+#define SPDL_ROWSPLIT(G, SEG)                                                                                  \
+  spmm_rowsplit_kernel<T, VEC, G, I, SEG><<<grid, block, 0, st>>>(m, n, ro, ci, val, order, B, C, bias, relu); \
   return SPDL_OK;
+  if (seg == 1) {
+    switch (li.lanes_per_row) {
+      case 8: SPDL_ROWSPLIT(8, 1)
+      case 16: SPDL_ROWSPLIT(16, 1)
+      case 32: SPDL_ROWSPLIT(32, 1)
+      case 64: SPDL_ROWSPLIT(64, 1)
+    }
+  } else if constexpr (VEC == 16 / (int)sizeof(T)) {
+    switch (li.lanes_per_row * 16 + seg) {
+      case 8 * 16 + 2: SPDL_ROWSPLIT(8, 2)
+      case 8 * 16 + 4: SPDL_ROWSPLIT(8, 4)
+      case 8 * 16 + 8: SPDL_ROWSPLIT(8, 8)
+      case 16 * 16 + 2: SPDL_ROWSPLIT(16, 2)
+      case 16 * 16 + 4: SPDL_ROWSPLIT(16, 4)
+      case 32 * 16 + 2: SPDL_ROWSPLIT(32, 2)
+    }
+  }
+#undef SPDL_ROWSPLIT
+  return SPDL_ERR_INVALID;
 }
 
 template <typename T, typename I>
@@ -294,9 +321,14 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
   if (variant < 0) {
     const double reuse = (m > 0 && k > 0) ? 64.0 * (double)nnz / ((double)m * (double)k) : 0.0;
     // wide dot products keep at most 32 nonzeros per row and 128-column slab in registers
+    // short dot products gain little from the slabs (a row of R is one or two cache lines) unless the
+    // reuse is high, and the nonzero-split kernel does not care how the entries are laid out (a
+    // banded attention mask leaves most of a panel's column ranges nearly empty)
+    const bool worth = n >= 128 || reuse >= 12.0;
     const bool fits = n <= 128 || 128.0 * (double)nnz / ((double)m * (double)k) <= 16.0;
     variant = !fast_ok ? kSddmmRowstrip
-              : (sizeof(T) == 4 && reuse >= 2.0 && m >= 512 && fits && nnz < (1 << 29)) ? kSddmmSlabDma : kSddmmGroup;
+              : (sizeof(T) == 4 && reuse >= 2.0 && worth && m >= 512 && fits && nnz < (1 << 29)) ? kSddmmSlabDma
+                                                                                                  : kSddmmGroup;
   }
   if ((variant == kSddmmSlab || variant == kSddmmSlabDma) &&
       !(fast_ok && sizeof(T) == 4 && nnz < (1 << 29) && n < (1 << 21)))   // 32-bit byte offsets

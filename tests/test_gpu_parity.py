@@ -251,11 +251,15 @@ def test_forced_spmm_variants_ragged(g, oracle_lib, force, n):
         if spdl.spdl_variant_name(0, v) == "mfma":
             continue                                      # fp16 only, see the mixed-precision tests
         force(0, v)
-        assert spdl.spdl_select_spmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"] == v
+        sel = spdl.spdl_select_spmm(A.m, A.k, n, A.nnz, 4, 0, 0)
+        assert sel["variant"] == v
         got = g.gpu_spmm(A, B, n, order)
         g.assert_close(got, C, S, g.TOL_F32, f"variant {spdl.spdl_variant_name(0, v)} n={n}")
-        results.append(got)
+        # (when several lane groups share a row, the row-splitting kernel adds partial sums)
+        if sel["block_threads"] != 256 or sel["rows_per_block"] * sel["lanes_per_row"] == 256:
+            results.append(got)
     # every family adds a row's products in stored order with fused multiply-adds: same bits
+    assert len(results) >= 2
     for r in results[1:]:
         assert np.array_equal(r, results[0])
 
@@ -355,3 +359,23 @@ def test_mfma_kernels_are_the_default_for_moderately_sparse_fp16(g):
     # fp32 never takes them, n % 8 != 0 neither
     assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(1024, 1024, 3136, 104000, 4, 0, 0)["variant"]) != "mfma"
     assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(1024, 1024, 3132, 104000, 2, 0, 0)["variant"]) == "rowsplit"
+
+
+def test_rowsplit_with_several_lane_groups_per_row(g, oracle_lib, force):
+    # few long rows: the row-splitting kernel spreads each row over 2, 4 or 8 lane groups
+    import paper_2006_10901_amd as spdl
+    force(0, 0)
+    seen = set()
+    for m, k, dens, n, dt in ((300, 4000, 0.3, 64, np.float32), (64, 3000, 0.5, 32, np.float32),
+                              (500, 2000, 0.2, 128, np.float32), (300, 4000, 0.3, 64, np.float16),
+                              (40, 5000, 0.4, 200, np.float32)):
+        A = wl.uniform_mask_csr(m, k, dens, 3000 + m)
+        A.row_offsets = A.row_offsets.copy()
+        if dt == np.float16:
+            A.values = A.values.astype(np.float16)
+        B = wl.dense(k, n, 3001 + m, dt)
+        sel = spdl.spdl_select_spmm(m, k, n, A.nnz, 2 if dt == np.float16 else 4, 0, 0)
+        seen.add(256 // (sel["rows_per_block"] * sel["lanes_per_row"]))
+        spmm_case(g, oracle_lib, A, B, n, g.TOL_F16 if dt == np.float16 else g.TOL_F32, "sorted",
+                  f"rowsplit segments m={m} n={n} {dt.__name__}")
+    assert max(seen) >= 4 and len(seen) >= 2, seen
