@@ -46,7 +46,9 @@ typedef enum {
  *               handed to workgroups (paper Sec. "Row Swizzle Load Balancing"); NULL = identity.
  *               The result does not depend on it.
  *   B : DEVICE fp32[k*n];   C : DEVICE fp32[m*n], fully overwritten (empty rows become +0).
- *   fp32 fused multiply-add accumulation in the stored order of each row. */
+ *   Products and sums are fp32 (fused multiply-adds).  Most kernels add a row's products in
+ *   stored order; when few long rows are spread over several lane groups, partial sums are added
+ *   at the end.  Either way the result is deterministic and does not depend on row_order. */
 int spdl_spmm(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
               const float* values, const int* row_order, const float* B, float* C, void* stream);
 
