@@ -138,6 +138,9 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
   if (variant == kSpmmMfma && (!mfma_ok || nnz == 0)) variant = kSpmmRowsplit;   // nnz == 0: B may be null
   if (variant < 0 && mfma_ok && mfma_dense_enough(m, k, nnz)) variant = kSpmmMfma;
   if (variant == kSpmmMfma) {
+    // 32-row panels, kSpmmMfmaWaves tiles per workgroup.  (64-row panels, which would halve the
+    // reads of B, need 256 accumulator registers per lane; the compiler then spills in the main
+    // loop and the kernel is twice as slow.)
     const int tiles_n = (n + 255) / 256;
     info->variant = kSpmmMfma;
     info->vec = 8;
@@ -221,16 +224,16 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const I* ci, const T*
   constexpr bool kInt32 = sizeof(I) == 4;        // the slab kernels read 32-bit indices only
   if (li.variant == kSpmmMfma) {
     if constexpr (sizeof(T) == 2) {
-      static std::atomic<int> configured{0};
-      const int lds = spmm_mfma_lds_bytes(k, kSpmmMfmaWaves);
-      auto kernel = spmm_mfma_kernel<kSpmmMfmaWaves, kSpmmMfmaKParts, I>;
-      if (configured.load() < lds) {
+      static std::atomic<bool> configured{false};
+      auto kernel = spmm_mfma_kernel<kSpmmMfmaWaves, kSpmmMfmaKParts, I, 1>;
+      if (!configured.load()) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                spmm_mfma_lds_bytes(kMfmaChunk, kSpmmMfmaWaves)) != hipSuccess)
+                                spmm_mfma_lds_bytes(kMfmaChunk, kSpmmMfmaWaves, 1)) != hipSuccess)
           return SPDL_ERR_LAUNCH;
-        configured.store(spmm_mfma_lds_bytes(kMfmaChunk, kSpmmMfmaWaves));
+        configured.store(true);
       }
-      kernel<<<dim3(li.grid_x), dim3(li.block_threads), lds, st>>>(m, k, n, li.grid_y, ro, ci, val, B, C, bias, relu);
+      kernel<<<dim3(li.grid_x), dim3(li.block_threads), spmm_mfma_lds_bytes(k, kSpmmMfmaWaves, 1), st>>>(
+          m, k, n, li.grid_y, ro, ci, val, B, C, bias, relu);
     } else {
       return SPDL_ERR_UNSUPPORTED;
     }
