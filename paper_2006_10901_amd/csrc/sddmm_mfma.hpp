@@ -3,8 +3,7 @@
 // vector rate, so for the moderately sparse matrices of deep learning it is cheaper to compute
 // a whole 32x32 block of L R^T with MFMA and keep only the entries A stores there than to
 // gather one row of R per stored entry.  The contraction runs over n, which is the contiguous
-// dimension of both row-major operands, so every lane loads its operand fragments straight
-// from global memory, 16 bytes at a time; nothing is staged.
+// dimension of both row-major operands.
 //
 // A workgroup owns one 64x64 block of A's index space.  Which stored entries fall into the
 // block: for each of its 64 rows a binary search gives the first entry with column >= c0 and
@@ -37,27 +36,48 @@ __device__ __attribute__((noinline)) float sddmm_lane_dot(const _Float16* __rest
   return acc;
 }
 
-constexpr int kSddmmMfmaLdsBytes = 4 * 64 * 65 * 4 + 2 * 64 * 4;
+constexpr int kSmK = 128;                              // columns of L and R per stage (16 pieces of 16 bytes)
+constexpr int kSmRing = 4;                             // stages resident in LDS (three being fetched)
+constexpr int kSmOperandBytes = 64 * kSmK * 2;         // 64 rows of one operand
+constexpr int kSmStageBytes = 2 * kSmOperandBytes;     // L rows, then R rows
+constexpr int kSddmmMfmaLdsBytes = kSmRing * kSmStageBytes + 2 * 64 * 4;   // the ring (reused for the block) + ranges
 
-// One workgroup (four waves) owns one 64x64 block of A's index space.  Each wave computes the
-// whole block, as 2x2 MFMA tiles, over a quarter of the contraction (four operand loads feed four
-// MFMAs: half the traffic per multiply of a 32x32 block, and four times the loads in flight
-// of one wave per block); the four partial blocks are laid side by side in LDS and added, in a
-// fixed order, only at the positions A stores.
+// One workgroup (four waves) owns one 64x64 block of A's index space and computes it as 2x2
+// MFMA tiles, one per wave.  The contraction runs over n, 128 columns per stage.  The 64 rows of
+// L and of R of the block are brought in by direct-to-LDS loads: sixteen lanes read the 256
+// contiguous bytes of one row, and each lane fetches the piece that belongs at its place in a
+// swizzled layout (piece p of row r at slot p xor (r mod 16)), so that the sixteen lanes of an
+// operand read, which want the same piece of sixteen rows, hit sixteen different bank groups.
+// Three stages are in flight while one is multiplied (a wave has little arithmetic per byte
+// here: the loads must be kept going); one barrier per stage.  The copies are issued from
+// inline assembly and waited for with explicit counts: they are the only vector-memory
+// operations inside the loop, and they complete in the order issued.  At the end the block goes
+// to LDS and the threads pick out the positions A stores.
+// (Measured and dropped: a fifth wave running ten stages ahead to pull the lines into L2, and
+// staging through registers instead of direct-to-LDS loads; both were slower.  With operands
+// that fit the L2s a stage costs 0.1 us, with the 13 MB of the 1x1 convolution 0.6 us.)
 __global__ __launch_bounds__(256) void sddmm_mfma_kernel(
     int m, int k, int n, int tiles_k, const int* __restrict__ row_offsets,
     const int* __restrict__ column_indices, const _Float16* __restrict__ L, const _Float16* __restrict__ R,
     _Float16* __restrict__ out, const _Float16* __restrict__ scale) {
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-  float (*part)[64][65] = reinterpret_cast<float (*)[64][65]>(lds_raw);          // [wave][row][column]
-  int (*bound)[64] = reinterpret_cast<int (*)[64]>(lds_raw + 4 * 64 * 65 * 4);   // [0]: range start, [1]: end
+  float (*block)[65] = reinterpret_cast<float (*)[65]>(lds_raw);                  // [row][column], after the loop
+  int (*bound)[64] = reinterpret_cast<int (*)[64]>(lds_raw + kSmRing * kSmStageBytes);   // [0]: range start, [1]: end
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
+  const int wi = wave >> 1, wc = wave & 1;             // this wave's 32x32 tile of the block
   const int r = lane & 31;
   const int half = lane >> 5;
-  const int tile_i = blockIdx.x / tiles_k;
-  const int tile_c = blockIdx.x - tile_i * tiles_k;
+  // Block id -> (tile_i, tile_c).  Consecutive workgroup ids go round-robin to the 8 XCDs, each
+  // with its own L2; XCD x gets the sub-grid (x/4 of 2 row halves) x (x%4 of 4 column quarters), so
+  // that its workgroups, which advance through n together, share the rows of L and R they stream.
+  const int tiles_m = (m + 63) >> 6;
+  const int TI = (tiles_m + 1) >> 1, TC = (tiles_k + 3) >> 2;
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int tile_i = (xcd >> 2) * TI + local / TC;
+  const int tile_c = (xcd & 3) * TC + local % TC;
+  if (tile_i >= tiles_m || tile_c >= tiles_k || local / TC >= TI) return;   // whole workgroup, before any barrier
   const int i0 = tile_i * 64;
   const int c0 = tile_c * 64;
 
@@ -81,93 +101,74 @@ __global__ __launch_bounds__(256) void sddmm_mfma_kernel(
     bound[which][tid & 63] = lo;
   }
 
-  // Partial block of L R^T over this wave's share of the 16-column steps.  Lane (r, half) holds
-  // columns 8*half .. 8*half+7 of a step, of rows i0+r and i0+32+r of L (first operands) and
-  // rows c0+r and c0+32+r of R (second operands); rows past the end of either matrix are clamped,
-  // their results are never looked at.
-  const int steps_all = (n + 15) >> 4;
-  const int per_wave = (steps_all + 3) >> 2;
-  const int s_begin = min(steps_all, wave * per_wave);
-  const int s_end = min(steps_all, s_begin + per_wave);
-  const int full_end = min(s_end, n >> 4);             // steps before this are complete for both halves
-  const _Float16* lp[2];
-  const _Float16* rp[2];
+  // Copies.  A stage is 32 copies of 1 KB (4 rows each); wave w issues copies 8w .. 8w+7: waves 0
+  // and 1 bring L, waves 2 and 3 bring R.  Copy j of a wave fills rows 4*(8*(w%2) + j) .. +3 of
+  // its operand; lane t brings row t/16 of those, the piece (t%16) xor (row%16), to slot t%16.
+  // Rows past the end of either matrix are clamped (their results are never looked at); pieces
+  // past column n are clamped to the stage's first piece and their products are zeroed below.
+  const int stages = (n + kSmK - 1) / kSmK;
+  const _Float16* operand = wave < 2 ? L : R;
+  const int row_limit = (wave < 2 ? m : k) - 1, row_base = wave < 2 ? i0 : c0;
+  unsigned voff[8];
+  int vpiece[8];
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    lp[b] = L + (size_t)min(i0 + 32 * b + r, m - 1) * n + 8 * half;
-    rp[b] = R + (size_t)min(c0 + 32 * b + r, k - 1) * n + 8 * half;
+  for (int j = 0; j < 8; ++j) {
+    const int row = 4 * (8 * (wave & 1) + j) + (lane >> 4);
+    vpiece[j] = (lane & 15) ^ (row & 15);
+    voff[j] = (unsigned)min(row_base + row, row_limit) * (unsigned)n * 2u;
   }
-  f32x16 acc[2][2];
+  const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds_raw;
+  auto issue_stage = [&](int s) {
+    const char* base = reinterpret_cast<const char*>(operand + (size_t)s * kSmK);
+    const unsigned dst = lds_base + (unsigned)((s % kSmRing) * kSmStageBytes + (wave >> 1) * kSmOperandBytes +
+                                               (wave & 1) * (kSmOperandBytes / 2));
 #pragma unroll
-  for (int bi = 0; bi < 2; ++bi)
-#pragma unroll
-    for (int bc = 0; bc < 2; ++bc)
-#pragma unroll
-      for (int t = 0; t < 16; ++t) acc[bi][bc][t] = 0.f;
-
-  constexpr int U = 4;                                  // steps per register set
-  f16x8 a0[U][2], b0v[U][2], a1[U][2], b1v[U][2];
-  auto load_set = [&](int s, f16x8 (&a)[U][2], f16x8 (&b)[U][2]) {
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        a[u][q] = load_h8(lp[q] + (s + u) * 16);
-        b[u][q] = load_h8(rp[q] + (s + u) * 16);
-      }
-  };
-  auto mma_set = [&](const f16x8 (&a)[U][2], const f16x8 (&b)[U][2]) {
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int bi = 0; bi < 2; ++bi)
-#pragma unroll
-        for (int bc = 0; bc < 2; ++bc)
-          acc[bi][bc] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[u][bi], b[u][bc], acc[bi][bc], 0, 0, 0);
-  };
-  // two register sets: the loads of one are in flight while the other is multiplied
-  int s = s_begin;
-  if (s + U <= full_end) load_set(s, a0, b0v);
-  for (; s + 2 * U <= full_end; s += 2 * U) {
-    load_set(s + U, a1, b1v);
-    mma_set(a0, b0v);
-    if (s + 3 * U <= full_end) load_set(s + 2 * U, a0, b0v);
-    mma_set(a1, b1v);
-  }
-  if (s + U <= full_end) {
-    mma_set(a0, b0v);
-    s += U;
-  }
-  // the remaining steps one at a time, the very last one possibly half empty (n % 16 == 8)
-  for (; s < s_end; ++s) {
-    const bool in = 16 * s + 8 * half < n;
-    // (the pointers already point 8*half columns into the row: step back for the lanes past the end)
-    const int o = in ? 16 * s : -8 * half;
-    f16x8 a[2], b[2];
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      a[q] = load_h8(lp[q] + o);
-      b[q] = load_h8(rp[q] + o);
-      if (!in) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) a[q][t] = b[q][t] = (_Float16)0.f;
-      }
+    for (int j = 0; j < 8; ++j) {
+      const bool in = s * kSmK + vpiece[j] * 8 < n;
+      const unsigned off = voff[j] + (in ? (unsigned)vpiece[j] * 16u : 0u);     // past n: the stage's first piece
+      const unsigned m0v = dst + (unsigned)j * 1024u;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :: "s"(m0v), "v"(off), "s"(base) : "memory");
     }
-#pragma unroll
-    for (int bi = 0; bi < 2; ++bi)
-#pragma unroll
-      for (int bc = 0; bc < 2; ++bc)
-        acc[bi][bc] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[bi], b[bc], acc[bi][bc], 0, 0, 0);
-  }
+  };
 
-  // Register t of lane (c, half) in tile (bi, bc) is element (32*bi + 8*(t/4) + 4*half + t%4, 32*bc + c).
+  f32x16 acc;
 #pragma unroll
-  for (int bi = 0; bi < 2; ++bi)
+  for (int t = 0; t < 16; ++t) acc[t] = 0.f;
+  // operand fragments: lane (r, half) reads piece 2u + half of row 32*wi + r of L and of row
+  // 32*wc + r of R, from their swizzled slots
+  const int arow = 32 * wi + r, brow = 32 * wc + r;
+  const int a_row_off = arow * (kSmK * 2), b_row_off = kSmOperandBytes + brow * (kSmK * 2);
+
 #pragma unroll
-    for (int bc = 0; bc < 2; ++bc)
+  for (int s = 0; s < kSmRing - 1; ++s)
+    if (s < stages) issue_stage(s);
+  for (int s = 0; s < stages; ++s) {
+    // stage s has arrived when at most the copies of the (up to two) later stages are outstanding
+    if (s + 2 < stages) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else if (s + 1 < stages) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                                   // everyone's copies of stage s are in; stage s-1 is consumed
+    if (s + kSmRing - 1 < stages) issue_stage(s + kSmRing - 1);
+    const char* buf = lds_raw + (s % kSmRing) * kSmStageBytes;
+    const bool ragged = (s + 1) * kSmK > n;
 #pragma unroll
-      for (int t = 0; t < 16; ++t)
-        part[wave][32 * bi + 8 * (t / 4) + 4 * half + (t % 4)][32 * bc + r] = acc[bi][bc][t];
+    for (int u = 0; u < kSmK / 16; ++u) {
+      const int p = 2 * u + half;
+      f16x8 a = *reinterpret_cast<const f16x8*>(buf + a_row_off + ((p ^ (arow & 15)) << 4));
+      const f16x8 b = *reinterpret_cast<const f16x8*>(buf + b_row_off + ((p ^ (brow & 15)) << 4));
+      if (ragged && s * kSmK + p * 8 >= n) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) a[t] = (_Float16)0.f;
+      }
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
+    }
+  }
+  __syncthreads();                                     // the ring is free: it now holds the block
+
+  // Register t of lane (r, half) is element (32*wi + 8*(t/4) + 4*half + t%4, 32*wc + r) of the block.
+#pragma unroll
+  for (int t = 0; t < 16; ++t) block[32 * wi + 8 * (t / 4) + 4 * half + (t % 4)][32 * wc + r] = acc[t];
   __syncthreads();
 
   // Four threads per row take alternate entries of its range.
@@ -178,10 +179,10 @@ __global__ __launch_bounds__(256) void sddmm_mfma_kernel(
   for (int p = b0 + (tid & 3); p < b1; p += 4) {
     const int c = column_indices[p];
     const unsigned cc = (unsigned)(c - c0);
-    float v;
-    if (cc < 64u) v = ((part[0][rr][cc] + part[1][rr][cc]) + part[2][rr][cc]) + part[3][rr][cc];
-    else v = sddmm_lane_dot(L + (size_t)row * n, R + (size_t)c * n, n);
-    sddmm_store<_Float16>(out, scale, p, v);
+    float val;
+    if (cc < 64u) val = block[rr][cc];
+    else val = sddmm_lane_dot(L + (size_t)row * n, R + (size_t)c * n, n);
+    sddmm_store<_Float16>(out, scale, p, val);
   }
 }
 

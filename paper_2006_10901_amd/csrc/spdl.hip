@@ -317,7 +317,8 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
     info->lanes_per_row = kWave;
     info->rows_per_block = 64;
     info->block_threads = 256;
-    info->grid_x = (int)tiles;
+    // 8 XCDs x (half the row tiles, rounded up) x (a quarter of the column tiles, rounded up)
+    info->grid_x = 8 * (((m + 63) / 64 + 1) / 2) * (((k + 63) / 64 + 3) / 4);
     info->grid_y = (k + 63) / 64;               // 64-column blocks per panel (the grid is 1-D)
     return;
   }

@@ -138,7 +138,7 @@ def test_selection_uses_widest_aligned_vector(spdl):
     assert spdl.spdl_variant_name(1, d["variant"]) == "group" and d["rows_per_block"] == 64
     assert d["grid_x"] == (20000 + 255) // 256
     d = spdl.spdl_select_sddmm(1024, 1024, 3136, 100000, 2, 0, 0)            # one position in ten: dense blocks
-    assert spdl.spdl_variant_name(1, d["variant"]) == "mfma" and d["grid_x"] == 16 * 16
+    assert spdl.spdl_variant_name(1, d["variant"]) == "mfma" and d["grid_x"] == 8 * 8 * 4
     s = spdl.spdl_select_spmm(1024, 1024, 3136, 100000, 2, 0, 0)
     assert spdl.spdl_variant_name(0, s["variant"]) == "mfma" and s["grid_x"] == 32 * 7 and s["rows_per_block"] == 32 and s["block_threads"] == 256
     assert spdl.spdl_variant_name(0, 0) is not None and spdl.spdl_variant_name(0, 99) is None
