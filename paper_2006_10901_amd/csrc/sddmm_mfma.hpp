@@ -42,31 +42,37 @@ constexpr int kSmOperandBytes = 64 * kSmK * 2;         // 64 rows of one operand
 constexpr int kSmStageBytes = 2 * kSmOperandBytes;     // L rows, then R rows
 constexpr int kSddmmMfmaLdsBytes = kSmRing * kSmStageBytes + 2 * 64 * 4;   // the ring (reused for the block) + ranges
 
-// One workgroup (four waves) owns one 64x64 block of A's index space and computes it as 2x2
-// MFMA tiles, one per wave.  The contraction runs over n, 128 columns per stage.  The 64 rows of
-// L and of R of the block are brought in by direct-to-LDS loads: sixteen lanes read the 256
-// contiguous bytes of one row, and each lane fetches the piece that belongs at its place in a
-// swizzled layout (piece p of row r at slot p xor (r mod 16)), so that the sixteen lanes of an
-// operand read, which want the same piece of sixteen rows, hit sixteen different bank groups.
-// Three stages are in flight while one is multiplied (a wave has little arithmetic per byte
-// here: the loads must be kept going); one barrier per stage.  The copies are issued from
-// inline assembly and waited for with explicit counts: they are the only vector-memory
-// operations inside the loop, and they complete in the order issued.  At the end the block goes
-// to LDS and the threads pick out the positions A stores.
-// (Measured and dropped: a fifth wave running ten stages ahead to pull the lines into L2, and
-// staging through registers instead of direct-to-LDS loads; both were slower.  With operands
-// that fit the L2s a stage costs 0.1 us, with the 13 MB of the 1x1 convolution 0.6 us.)
+// One workgroup (four waves) owns one 64x64 block of A's index space.  The contraction runs
+// over n, 128 columns per stage.  The 64 rows of L and of R of the block are brought in by
+// direct-to-LDS loads: sixteen lanes read the 256 contiguous bytes of one row, and each lane
+// fetches the piece that belongs at its place in a swizzled layout (piece p of row r at slot
+// p xor (r mod 16)), so that the sixteen lanes of an operand read, which want the same piece of
+// sixteen rows, hit sixteen different bank groups.  Three stages are in flight while one is
+// multiplied (there is little arithmetic per byte here: the loads must be kept going); one
+// barrier per stage.  The copies are issued from inline assembly and waited for with explicit
+// counts: apart from two early index loads they are the only vector-memory operations inside
+// the loop, and they complete in the order issued.  At the end the partial blocks go to LDS and
+// the threads pick out the positions A stores.
+//
+// What bounds it: a CU pulls L2-resident data at some 120 GB/s at best and about 90 GB/s through
+// a ring with a barrier per stage (both measured with copy-only kernels), i.e. 0.35 us for a
+// 32 KB stage, against 0.1 us of MFMA; LDS reads compete with the copies' LDS writes, which is
+// why every byte is read only once (see the accumulators below).  Measured: 0.45 - 0.6 us per
+// stage.  Larger blocks would need fewer bytes per product but leave most CUs without a block at
+// the sizes of the 1x1 convolution (256 blocks of 64x64).
+// (Measured and dropped: a fifth wave running ahead to pull the lines into L2, staging through
+// registers instead of direct-to-LDS loads, and reading a stage's fragments one iteration ahead
+// of their MFMAs; none was faster.)
 __global__ __launch_bounds__(256) void sddmm_mfma_kernel(
     int m, int k, int n, int tiles_k, const int* __restrict__ row_offsets,
     const int* __restrict__ column_indices, const _Float16* __restrict__ L, const _Float16* __restrict__ R,
     _Float16* __restrict__ out, const _Float16* __restrict__ scale) {
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-  float (*block)[65] = reinterpret_cast<float (*)[65]>(lds_raw);                  // [row][column], after the loop
+  float (*part)[64][65] = reinterpret_cast<float (*)[64][65]>(lds_raw);           // [wave][row][column], after the loop
   int (*bound)[64] = reinterpret_cast<int (*)[64]>(lds_raw + kSmRing * kSmStageBytes);   // [0]: range start, [1]: end
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
-  const int wi = wave >> 1, wc = wave & 1;             // this wave's 32x32 tile of the block
   const int r = lane & 31;
   const int half = lane >> 5;
   // Block id -> (tile_i, tile_c).  Consecutive workgroup ids go round-robin to the 8 XCDs, each
@@ -80,26 +86,6 @@ __global__ __launch_bounds__(256) void sddmm_mfma_kernel(
   if (tile_i >= tiles_m || tile_c >= tiles_k || local / TC >= TI) return;   // whole workgroup, before any barrier
   const int i0 = tile_i * 64;
   const int c0 = tile_c * 64;
-
-  // Range of row i0 + t%64 that this block owns: threads 0..63 search for c0, 64..127 for c0 + 64.
-  if (tid < 128) {
-    const int row = i0 + (tid & 63);
-    const int which = tid >> 6;
-    int rs = 0, re = 0;
-    if (row < m) {
-      rs = row_offsets[row];
-      re = row_offsets[row + 1];
-    }
-    int lo = rs, hi = re;
-    const int key = c0 + 64 * which;
-    while (lo < hi) {
-      const int mid = (lo + hi) >> 1;
-      if (column_indices[mid] < key) lo = mid + 1; else hi = mid;
-    }
-    if (which == 0 && tile_c == 0) lo = rs;
-    if (which == 1 && tile_c == tiles_k - 1) lo = re;
-    bound[which][tid & 63] = lo;
-  }
 
   // Copies.  A stage is 32 copies of 1 KB (4 rows each); wave w issues copies 8w .. 8w+7: waves 0
   // and 1 bring L, waves 2 and 3 bring R.  Copy j of a wave fills rows 4*(8*(w%2) + j) .. +3 of
@@ -132,55 +118,104 @@ __global__ __launch_bounds__(256) void sddmm_mfma_kernel(
     }
   };
 
-  f32x16 acc;
+  // Every wave accumulates the whole 64x64 block over its quarter of each stage (columns
+  // 32*wave .. +31 of the stage's 128): every byte of a stage is then read from LDS once, by one
+  // wave, where a split of the block into four 32x32 tiles reads it twice (LDS reads and the copies'
+  // LDS writes share one port, and the tile split keeps it busier than the matrix cores).  The four
+  // partial blocks are added when the entries are sampled.
+  f32x16 acc[2][2];
 #pragma unroll
-  for (int t = 0; t < 16; ++t) acc[t] = 0.f;
-  // operand fragments: lane (r, half) reads piece 2u + half of row 32*wi + r of L and of row
-  // 32*wc + r of R, from their swizzled slots
-  const int arow = 32 * wi + r, brow = 32 * wc + r;
-  const int a_row_off = arow * (kSmK * 2), b_row_off = kSmOperandBytes + brow * (kSmK * 2);
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int t = 0; t < 16; ++t) acc[i][j][t] = 0.f;
+  // operand fragments: lane (r, half) reads piece 4*wave + 2*step + half of rows r and 32 + r of L
+  // and of R, from their swizzled slots (rows r and 32 + r share r % 16)
+  const int a_row_off = r * (kSmK * 2), b_row_off = kSmOperandBytes + r * (kSmK * 2);
 
 #pragma unroll
   for (int s = 0; s < kSmRing - 1; ++s)
     if (s < stages) issue_stage(s);
+
+  // Range of row i0 + t%64 that this block owns: threads 0..63 search for c0, 64..127 for c0 + 64
+  // (a chain of dependent loads: it runs while the first stages arrive).
+  if (tid < 128) {
+    const int row = i0 + (tid & 63);
+    const int which = tid >> 6;
+    int rs = 0, re = 0;
+    if (row < m) {
+      rs = row_offsets[row];
+      re = row_offsets[row + 1];
+    }
+    int lo = rs, hi = re;
+    const int key = c0 + 64 * which;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (column_indices[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    if (which == 0 && tile_c == 0) lo = rs;
+    if (which == 1 && tile_c == tiles_k - 1) lo = re;
+    bound[which][tid & 63] = lo;
+  }
+
+  int pre_b0 = 0, pre_b1 = 0, pre_c0 = 0, pre_c1 = 0;
   for (int s = 0; s < stages; ++s) {
     // stage s has arrived when at most the copies of the (up to two) later stages are outstanding
     if (s + 2 < stages) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     else if (s + 1 < stages) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();                                   // everyone's copies of stage s are in; stage s-1 is consumed
+    if (s == 0) {
+      // the ranges are visible now: fetch this thread's first two column indices, to be used after the loop
+      pre_b0 = bound[0][tid >> 2];
+      pre_b1 = max(pre_b0, bound[1][tid >> 2]);
+      const int p = pre_b0 + (tid & 3);
+      if (p < pre_b1) pre_c0 = column_indices[p];
+      if (p + 4 < pre_b1) pre_c1 = column_indices[p + 4];
+    }
     if (s + kSmRing - 1 < stages) issue_stage(s + kSmRing - 1);
     const char* buf = lds_raw + (s % kSmRing) * kSmStageBytes;
     const bool ragged = (s + 1) * kSmK > n;
 #pragma unroll
-    for (int u = 0; u < kSmK / 16; ++u) {
-      const int p = 2 * u + half;
-      f16x8 a = *reinterpret_cast<const f16x8*>(buf + a_row_off + ((p ^ (arow & 15)) << 4));
-      const f16x8 b = *reinterpret_cast<const f16x8*>(buf + b_row_off + ((p ^ (brow & 15)) << 4));
+    for (int step = 0; step < 2; ++step) {
+      const int p = 4 * wave + 2 * step + half;
+      const int slot = (p ^ (r & 15)) << 4;
+      f16x8 a0 = *reinterpret_cast<const f16x8*>(buf + a_row_off + slot);
+      f16x8 a1 = *reinterpret_cast<const f16x8*>(buf + a_row_off + 32 * (kSmK * 2) + slot);
+      const f16x8 b0 = *reinterpret_cast<const f16x8*>(buf + b_row_off + slot);
+      const f16x8 b1 = *reinterpret_cast<const f16x8*>(buf + b_row_off + 32 * (kSmK * 2) + slot);
       if (ragged && s * kSmK + p * 8 >= n) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) a[t] = (_Float16)0.f;
+        for (int t = 0; t < 8; ++t) a0[t] = a1[t] = (_Float16)0.f;
       }
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b1, acc[1][1], 0, 0, 0);
     }
   }
-  __syncthreads();                                     // the ring is free: it now holds the block
+  __syncthreads();                                     // the ring is free: it now holds the four partial blocks
 
-  // Register t of lane (r, half) is element (32*wi + 8*(t/4) + 4*half + t%4, 32*wc + r) of the block.
+  // Register t of lane (r, half) in acc[i][j] is element (32*i + 8*(t/4) + 4*half + t%4, 32*j + r).
+  float (*mine)[65] = part[wave];
 #pragma unroll
-  for (int t = 0; t < 16; ++t) block[32 * wi + 8 * (t / 4) + 4 * half + (t % 4)][32 * wc + r] = acc[t];
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int t = 0; t < 16; ++t) mine[32 * i + 8 * (t / 4) + 4 * half + (t % 4)][32 * j + r] = acc[i][j][t];
   __syncthreads();
 
   // Four threads per row take alternate entries of its range.
   const int rr = tid >> 2;
   const int row = i0 + rr;
-  const int b0 = bound[0][rr];
-  const int b1 = max(b0, bound[1][rr]);
-  for (int p = b0 + (tid & 3); p < b1; p += 4) {
-    const int c = column_indices[p];
+  const int b0 = pre_b0, b1 = pre_b1;
+  for (int p = b0 + (tid & 3), it = 0; p < b1; p += 4, ++it) {
+    const int c = it == 0 ? pre_c0 : it == 1 ? pre_c1 : column_indices[p];
     const unsigned cc = (unsigned)(c - c0);
     float val;
-    if (cc < 64u) val = block[rr][cc];
+    if (cc < 64u) val = (part[0][rr][cc] + part[1][rr][cc]) + (part[2][rr][cc] + part[3][rr][cc]);
     else val = sddmm_lane_dot(L + (size_t)row * n, R + (size_t)c * n, n);
     sddmm_store<_Float16>(out, scale, p, val);
   }

@@ -134,7 +134,7 @@ inline bool mfma_dense_enough(int m, int k, int nnz) { return 32.0 * (double)nnz
 template <typename T>
 void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, spdl_launch_info* info) {
   int variant = g_forced[0].load();
-  const bool mfma_ok = sizeof(T) == 2 && n % 8 == 0 && n < (1 << 24) && aligned(B, 16) && aligned(C, 16);
+  const bool mfma_ok = sizeof(T) == 2 && n % 8 == 0 && n < (1 << 24) && k >= 16 && aligned(B, 16) && aligned(C, 16);
   if (variant == kSpmmMfma && (!mfma_ok || nnz == 0)) variant = kSpmmRowsplit;   // nnz == 0: B may be null
   if (variant < 0 && mfma_ok && mfma_dense_enough(m, k, nnz)) variant = kSpmmMfma;
   if (variant == kSpmmMfma) {
