@@ -349,6 +349,29 @@ def test_mfma_kernels_edge_cases(g, oracle_lib, force, n):
         sddmm_case(g, oracle_lib, A, L, R, n, g.TOL_F16, f"group sddmm f16 n={n}")
 
 
+def test_mfma_spmm_row_lengths_and_short_contractions(g, oracle_lib, force):
+    # Row lengths around the sizes the panel expansion works in (64 entries per load, 128 fetched
+    # ahead, 256 per further round), and contractions shorter than the depth of the pipeline of B
+    # loads (16 rows per step, six steps in registers), with and without a ragged last step.
+    import paper_2006_10901_amd as spdl
+    lengths = [0, 1, 63, 64, 65, 127, 128, 129, 191, 192, 193, 383, 384, 385, 640, 1500, 0, 2, 700, 130] * 2
+    cases = [wl.row_lengths_csr(len(lengths), 1500, lengths, 1200)]
+    for k in (16, 17, 31, 32, 40, 95, 96, 97, 112):
+        cases.append(wl.uniform_mask_csr(50, k, 0.6, 1201 + k))
+    for A in cases:
+        A = _f16(A)
+        for n in (8, 264):
+            B = wl.dense(A.k, n, 1250 + n, np.float16)
+            force(0, 3)
+            assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(A.m, A.k, n, A.nnz, 2, 0, 0)["variant"]) == "mfma"
+            spmm_case(g, oracle_lib, A, B, n, g.TOL_F16, "sorted", f"mfma spmm n={n} m={A.m} k={A.k}")
+    # below 16 columns of A the kernel is not taken, forced or not
+    A = _f16(wl.uniform_mask_csr(50, 12, 0.6, 1290))
+    force(0, 3)
+    assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(A.m, A.k, 64, A.nnz, 2, 0, 0)["variant"]) == "rowsplit"
+    spmm_case(g, oracle_lib, A, wl.dense(A.k, 64, 1291, np.float16), 64, g.TOL_F16, "sorted", "k=12 fp16")
+
+
 def test_mfma_kernels_are_the_default_for_moderately_sparse_fp16(g):
     import paper_2006_10901_amd as spdl
     assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(1024, 1024, 3136, 104000, 2, 0, 0)["variant"]) == "mfma"
