@@ -78,6 +78,17 @@ template <> struct Pack<_Float16, 8> {
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Maximum of two wave-uniform values on the scalar unit (left to itself the compiler moves such
+// a maximum to the vector unit as soon as one of its uses is a vector select).
+__device__ __forceinline__ int scalar_max(int a, int b) {
+  int r;
+  asm("s_max_i32 %0, %1, %2" : "=s"(r) : "s"(a), "s"(b) : "scc");
+  return r;
+}
+
+// Number of leading set bits of a 16-bit piece of a wave mask (scalar arithmetic).
+__device__ __forceinline__ int leading16(unsigned piece) { return __builtin_ctz(~piece | 0x10000u); }
+
 // Workgroup id -> (panel of sparse rows, group = slice of the dense operand) for the slab kernels.
 // Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2: all
 // groups of a panel get ids that are equal modulo 8, so the panel's part of A is fetched into

@@ -1,0 +1,376 @@
+// SDDMM, lane family (fp32, dot products of up to 128 columns): the slab decomposition (a
+// workgroup owns a panel of sparse rows and a run of slabs of R, streamed through LDS by
+// direct-to-LDS copies; paper Sec. "Sampled Dense--Dense Matrix Multiplication Operation" for
+// the strips of consecutive nonzeros), but every nonzero's dot product is formed by four lanes
+// from start to end, each on its own quarter of the columns.  No partial sums are transposed
+// across the group, no address is formed per LDS read, and both operands of every multiply-add
+// are in the lane's own registers: a plain v_fmac_f32 issues in about three clocks per wave on
+// this chip, the forms that take an operand from another lane (DPP) or from a scalar register in
+// four and a half.
+//
+// A 16-lane group works on a strip of 4 consecutive nonzeros of one sparse row.  Lane 4t+h
+// (t = 0..3, h = 0..3) owns nonzero t and quarter h of the dot product (columns 32h .. 32h+31).
+// In step s = 0..3 it multiplies the eight columns 32h + 8((t-s) mod 4) .. of its quarter: its
+// R row supplies them with two 16-byte LDS reads at a fixed offset from the row's address, and
+// the matching values of L sit in registers, loaded once per kernel in exactly the order the
+// lane will use them (32 registers per sparse row).  The four quarters are added with two quad
+// permutes.  Per nonzero and lane: 32 multiply-adds, 4 address additions, 8 LDS reads.
+//
+// Bank conflicts: the 16 lanes of a group read 16 different rows of R at once, so the layout
+// alone cannot keep them apart; the rotation by t does.  A slab holds the two 64-column halves
+// of its rows in two regions of 256-byte rows, the second region shifted by 16 bytes.  In step s
+// lane 4t+h reads bytes 128(h mod 2) + 32((t-s) mod 4) .. +31 of a row in region h/2: over the
+// group these are the sixteen different 16-byte bank groups of the 64 banks, whatever the rows.
+//
+// Lanes whose nonzero does not exist (ragged strip, row done in this slab) read the first row
+// of the slab and their result is dropped: nothing outside a nonzero's own rows of L and R can
+// reach its output.
+//
+// Stage pipeline: the copy of the next slab and the loads of the next column indices are issued
+// at the start of a stage, the results of a stage are stored at the start of the next one, and
+// every stage ends with a wait for everything plus a barrier: whatever is waited for has had the
+// whole stage to complete.
+//
+// Rows must be ascending for the slab walk; a row that is not is noticed when its nonzeros
+// inside a slab are not a prefix of the look-ahead, its cursor is frozen, and the row is redone
+// by direct gathers after the last slab.
+// Needs n % 4 == 0, n <= 128, 16-byte aligned L and R.
+#pragma once
+#include "common.hpp"
+#include "sddmm_slab.hpp"
+
+namespace spdl {
+
+constexpr int kLaneS = 128;                          // rows of R per slab
+constexpr int kLaneRegion = kLaneS * 256 + 16;       // one 64-column half of a slab
+constexpr int kLaneBuf = 2 * kLaneRegion;
+constexpr int kLaneLdsBytes = 2 * kLaneBuf;
+
+// The two 16-byte LDS reads of one step: 32 bytes of the R row at byte offset `off`, from x on.
+__device__ __forceinline__ void lane_read(const char* lds, int off, int x, f32x4& b0, f32x4& b1) {
+  const char* a = lds + (off + x);
+  b0 = *reinterpret_cast<const f32x4*>(a);
+  b1 = *reinterpret_cast<const f32x4*>(a + 16);
+}
+
+// Sum of v over the 16 lanes of a group, in every lane (four DPP row rotations).
+__device__ __forceinline__ int group_sum16(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x128 /* row_ror:8 */, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x124 /* row_ror:4 */, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x122 /* row_ror:2 */, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x121 /* row_ror:1 */, 0xf, 0xf, false);
+  return v;
+}
+
+// Value of lane Q of each quad, in all four lanes of the quad.
+template <int Q>
+__device__ __forceinline__ int quad_bcast(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, Q * 0x55 /* quad_perm [Q,Q,Q,Q] */, 0xf, 0xf, false);
+}
+
+// Sum of a over the four lanes of a quad, in every lane.
+__device__ __forceinline__ float quad_sum(float a) {
+  a += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0xb1 /* [1,0,3,2] */,
+                                                             0xf, 0xf, false));
+  a += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x4e /* [2,3,0,1] */,
+                                                             0xf, 0xf, false));
+  return a;
+}
+
+// RPG  = sparse rows per 16-lane group: the workgroup owns 64*RPG consecutive rows.
+// NCHD = the look-ahead per row, in chunks of 16 column indices: a row may have up to 16*NCHD
+//        nonzeros in one slab before it needs a second round in that slab (a full wait).
+template <int RPG, int NCHD, bool SCALED>
+__global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
+    int m, int k, int n, int nnz, int ksplit, int slabs_per_part, int panels,
+    const int* __restrict__ row_offsets, const int* __restrict__ column_indices,
+    const float* __restrict__ L, const float* __restrict__ R, float* __restrict__ out,
+    const float* __restrict__ scale) {
+  constexpr int S = kLaneS;
+  constexpr int WIN = 16 * NCHD;                // nonzeros per round
+  constexpr int kCopies = S * 2 / 4 / 16;       // 1 KB direct-to-LDS loads per wave per slab
+  extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = uniform(tid >> 6);
+  const int sub = lane >> 4;
+  const int l16 = lane & 15;
+  const int t4 = l16 >> 2;
+  const int h4 = l16 & 3;
+  // Position inside a chunk of 16 nonzeros of the one whose column index this lane loads (and
+  // whose result it stores): strip q of the chunk is nonzeros 4q .. 4q+3, nonzero 4q+t is
+  // worked on by the quad t and kept by its lane q.
+  const int perm = 4 * h4 + t4;
+  const int last_nz = nnz - 1;
+
+  int panel, kpart;
+  if (!slab_wg_map(blockIdx.x, panels, ksplit, panel, kpart)) return;
+  const int k0 = kpart * slabs_per_part * S;
+  const int k1 = min(k, k0 + slabs_per_part * S);
+  const int nslabs = (k1 - k0 + S - 1) / S;
+
+  // Slab copy: copy i of wave w moves four rows of one region (1 KB); lane L brings 16 bytes of
+  // row L/16, and the hardware places lane L's bytes at M0 + 16 L.  The address is a scalar
+  // base (start of the slab in R) plus a per-lane byte offset that is the same in every stage
+  // except the last slab, whose rows past k are clamped to row k-1; columns past n are clamped
+  // to the row's first columns (the matching values of L are zero).  S * n * 4 < 2^31 is
+  // checked on the host.
+  unsigned src_off[kCopies], src_off_last[kCopies];
+  int dst_off[kCopies];
+  const int last_rows = k - (k0 + (nslabs - 1) * S);          // rows of R from the last slab's start
+#pragma unroll
+  for (int i = 0; i < kCopies; ++i) {
+    const int idx = i * 16 + wave;
+    const int reg = idx & 1, rblock = idx >> 1;
+    const int lrow = rblock * 4 + sub;
+    const int col = reg * 64 + l16 * 4;
+    const unsigned colb = col < n ? (unsigned)col * 4u : 0u;
+    src_off[i] = (unsigned)lrow * (unsigned)n * 4u + colb;
+    src_off_last[i] = (unsigned)min(lrow, last_rows - 1) * (unsigned)n * 4u + colb;
+    dst_off[i] = reg * kLaneRegion + rblock * 1024;
+  }
+  const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds_raw;
+  // Issued from inline assembly: the compiler counts its own direct-to-LDS loads on both memory
+  // counters and then turns every later wait into a wait for everything; their completion is
+  // covered by the explicit full wait that ends every stage.
+  auto copy_stage = [&](int q) {
+    const char* base = reinterpret_cast<const char*>(R + (size_t)(k0 + q * S) * n);
+    const unsigned dst = lds_base + (unsigned)((q & 1) * kLaneBuf);
+    const bool last = q == nslabs - 1;
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i) {
+      const unsigned voff = last ? src_off_last[i] : src_off[i];
+      const unsigned m0v = dst + (unsigned)dst_off[i];
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :: "s"(m0v), "v"(voff), "s"(base) : "memory", "m0");
+    }
+  };
+
+  // rows of this group, their ranges of nonzeros inside [k0, k1), their quarters of L in the
+  // order of use: lr[j][8 s + e] = L[row, 32 h + 8((t-s) mod 4) + e]
+  int row[RPG], p_end[RPG], p[RPG];
+  float lr[RPG][32];
+  bool safe = true;                  // no load of the look-ahead can pass the end of the arrays
+#pragma unroll
+  for (int j = 0; j < RPG; ++j) {
+    const int r = (panel * kSdRows + wave * 4 + sub) * RPG + j;
+    const bool ok = r < m;
+    row[j] = ok ? r : -1;
+    const int rb = ok ? row_offsets[r] : 0;
+    const int re = ok ? row_offsets[r + 1] : 0;
+    p[j] = k0 <= 0 ? rb : sd_lower_bound16(column_indices, rb, re, k0, sub, l16, last_nz);
+    p_end[j] = k1 >= k ? re : sd_lower_bound16(column_indices, rb, re, k1, sub, l16, last_nz);
+    p_end[j] = max(p_end[j], p[j]);
+    safe = safe && __builtin_amdgcn_ballot_w64(p_end[j] + WIN > nnz) == 0;
+    const float* lrow = L + (size_t)(ok ? r : 0) * n;
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int c = 32 * h4 + 8 * ((t4 - s) & 3) + 4 * u;
+        const bool in = ok && c < n;
+        const f32x4 vv = *reinterpret_cast<const f32x4*>(lrow + (in ? c : 0));
+        lr[j][8 * s + 4 * u + 0] = in ? vv.x : 0.f;
+        lr[j][8 * s + 4 * u + 1] = in ? vv.y : 0.f;
+        lr[j][8 * s + 4 * u + 2] = in ? vv.z : 0.f;
+        lr[j][8 * s + 4 * u + 3] = in ? vv.w : 0.f;
+      }
+  }
+  // byte offset of step s inside this lane's 256-byte row (the region is added to the row base)
+  int x[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) x[s] = (h4 & 1) * 128 + ((t4 - s) & 3) * 32;
+
+  // Look-ahead of row j from position `from`: the next 16*NCHD column indices, lane 4t+h of the
+  // group holding index 16 i + 4 h + t of chunk i; with them the values of A if the results are
+  // to be scaled.  Raw loads, first used in the next stage.  32-bit byte offsets from scalar
+  // bases (nnz < 2^29 is checked on the host).
+  int cn[RPG][NCHD];
+  float sc[RPG][SCALED ? NCHD : 1];
+  auto fetch = [&](int j, int from) {
+    const char* cbase = reinterpret_cast<const char*>(column_indices);
+    const char* vbase = reinterpret_cast<const char*>(scale);
+    if (safe) {
+      const unsigned o = (unsigned)(from + perm) << 2;
+#pragma unroll
+      for (int i = 0; i < NCHD; ++i) {
+        cn[j][i] = *reinterpret_cast<const int*>(cbase + (o + 64u * i));
+        if (SCALED) sc[j][i] = *reinterpret_cast<const float*>(vbase + (o + 64u * i));
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NCHD; ++i) {
+        const unsigned o = (unsigned)min(from + perm + 16 * i, last_nz) << 2;
+        cn[j][i] = *reinterpret_cast<const int*>(cbase + o);
+        if (SCALED) sc[j][i] = *reinterpret_cast<const float*>(vbase + o);
+      }
+    }
+  };
+
+  // results of the previous round, stored at the start of the next one: this lane's nonzero of
+  // chunk i of row j goes to out[st_pos[j] + 16 i] if the lane is in st_mask[j][i]
+  float outv[RPG][NCHD];
+  int st_off[RPG];
+  unsigned long long st_mask[RPG][NCHD];
+#pragma unroll
+  for (int j = 0; j < RPG; ++j)
+#pragma unroll
+    for (int i = 0; i < NCHD; ++i) st_mask[j][i] = 0;
+  auto store_pending = [&]() {
+#pragma unroll
+    for (int j = 0; j < RPG; ++j) {
+      float* o = reinterpret_cast<float*>(reinterpret_cast<char*>(out) + (unsigned)st_off[j]);
+#pragma unroll
+      for (int i = 0; i < NCHD; ++i) {
+        if (st_mask[j][i] == 0) break;
+        if (__builtin_amdgcn_inverse_ballot_w64(st_mask[j][i])) o[16 * i] = outv[j][i];
+        st_mask[j][i] = 0;
+      }
+    }
+  };
+
+  copy_stage(0);
+#pragma unroll
+  for (int j = 0; j < RPG; ++j) fetch(j, p[j]);
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+
+  for (int s = 0; s < nslabs; ++s) {
+    const int slab_start = k0 + s * S;
+    const int buf_off = (s & 1) * kLaneBuf;
+    // LDS byte offset of R row c in this lane's region = (c << 8) + row_base
+    const int row_base = buf_off + (h4 >> 1) * kLaneRegion - slab_start * 256;
+    bool first = true, more;
+    do {
+      // A use of every look-ahead register before the copies are issued: the compiler places its
+      // wait for those loads here, where they completed long ago (full wait at the end of the
+      // previous stage), instead of after the copies, where it would wait for those too.
+#pragma unroll
+      for (int j = 0; j < RPG; ++j)
+#pragma unroll
+        for (int i = 0; i < NCHD; ++i) {
+          asm volatile("" :: "v"(cn[j][i]));
+          if (SCALED) asm volatile("" :: "v"(sc[j][i]));
+        }
+      store_pending();
+      if (first && s + 1 < nslabs) copy_stage(s + 1);
+      first = false;
+      more = false;
+      // First the look-ahead of every row is counted and replaced by the next one, so that all
+      // loads of a stage are issued before its arithmetic starts; then the strips are worked on.
+      int col[RPG][NCHD], vl[RPG];
+      float scv[RPG][SCALED ? NCHD : 1];
+      unsigned long long okm[RPG][NCHD];
+#pragma unroll
+      for (int j = 0; j < RPG; ++j) {
+        // How many of the fetched nonzeros fall into this slab.  Every lane looks at its own
+        // position of each chunk; in an ascending row the positions inside the slab and the row
+        // are a prefix of the look-ahead, so their number is the sum of the lanes' counts.  If
+        // they are not exactly the first `used` positions the row is not ascending: its cursor
+        // is frozen (p_end is never reached) and the row is redone after the last slab.
+        const int remain_l = p_end[j] - p[j] - perm;
+        int nv = 0;
+#pragma unroll
+        for (int i = 0; i < NCHD; ++i) {
+          okm[j][i] = __builtin_amdgcn_ballot_w64((unsigned)(cn[j][i] - slab_start) < (unsigned)S) &
+                      __builtin_amdgcn_ballot_w64(remain_l > 16 * i);
+          nv += __builtin_amdgcn_inverse_ballot_w64(okm[j][i]) ? 1 : 0;
+        }
+        int used = group_sum16(nv);
+        const int used_l = used - perm;
+        unsigned long long bad = 0;
+#pragma unroll
+        for (int i = 0; i < NCHD; ++i) bad |= okm[j][i] ^ __builtin_amdgcn_ballot_w64(used_l > 16 * i);
+        if (bad != 0) {                                 // wave-uniform, rare
+          if (((unsigned)(bad >> (sub * 16)) & 0xffffu) != 0) { used = 0; p_end[j] = -1; }
+#pragma unroll
+          for (int i = 0; i < NCHD; ++i) okm[j][i] = __builtin_amdgcn_ballot_w64(used - perm > 16 * i);
+        }
+        more = more || __builtin_amdgcn_ballot_w64(used == WIN) != 0;
+        vl[j] = used - t4;       // this quad's nonzero of strip q of chunk i exists if vl > 16 i + 4 q
+        st_off[j] = (p[j] + perm) << 2;
+        p[j] += used;
+        // the column indices are moved out of the way of the next look-ahead
+#pragma unroll
+        for (int i = 0; i < NCHD; ++i) {
+          col[j][i] = cn[j][i];
+          if (SCALED) scv[j][i] = sc[j][i];
+        }
+        fetch(j, p[j]);
+      }
+#pragma unroll
+      for (int j = 0; j < RPG; ++j) {
+        // Software pipeline over (strip, step): LDS reads run two steps ahead of the
+        // multiply-adds, also across strips, through two register sets used in turn; reads
+        // for a strip that does not exist hit a valid address and are dropped.
+        auto strip_off = [&](int i, int q) -> int {
+          int c;
+          switch (q) {
+            case 0: c = quad_bcast<0>(col[j][i]); break;
+            case 1: c = quad_bcast<1>(col[j][i]); break;
+            case 2: c = quad_bcast<2>(col[j][i]); break;
+            default: c = quad_bcast<3>(col[j][i]); break;
+          }
+          return vl[j] > 16 * i + 4 * q ? (c << 8) + row_base : buf_off;
+        };
+        f32x4 b[2][2];
+        int off = strip_off(0, 0);
+        lane_read(lds_raw, off, x[0], b[0][0], b[0][1]);
+        lane_read(lds_raw, off, x[1], b[1][0], b[1][1]);
+        bool done = false;
+#pragma unroll
+        for (int i = 0; i < NCHD; ++i) {
+          if (done) break;
+          float keep = 0.f;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            if (__builtin_amdgcn_ballot_w64(vl[j] > 16 * i + 4 * q) == 0) { done = true; break; }
+            const bool last_strip = i == NCHD - 1 && q == 3;
+            const int off_next = last_strip ? off : strip_off(q == 3 ? i + 1 : i, q == 3 ? 0 : q + 1);
+            float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+              const f32x4 b0 = b[st & 1][0], b1 = b[st & 1][1];
+              const float* l = &lr[j][8 * st];
+              acc0 = __builtin_fmaf(l[0], b0.x, acc0);
+              acc1 = __builtin_fmaf(l[1], b0.y, acc1);
+              acc0 = __builtin_fmaf(l[2], b0.z, acc0);
+              acc1 = __builtin_fmaf(l[3], b0.w, acc1);
+              acc0 = __builtin_fmaf(l[4], b1.x, acc0);
+              acc1 = __builtin_fmaf(l[5], b1.y, acc1);
+              acc0 = __builtin_fmaf(l[6], b1.z, acc0);
+              acc1 = __builtin_fmaf(l[7], b1.w, acc1);
+              if (st < 2) lane_read(lds_raw, off, x[st + 2], b[st & 1][0], b[st & 1][1]);
+              else if (!last_strip) lane_read(lds_raw, off_next, x[st - 2], b[st & 1][0], b[st & 1][1]);
+            }
+            const float total = quad_sum(acc0 + acc1);
+            keep = h4 == q ? total : keep;
+            off = off_next;
+          }
+          outv[j][i] = SCALED ? keep * scv[j][i] : keep;
+          st_mask[j][i] = okm[j][i];
+        }
+      }
+      if (more) __builtin_amdgcn_s_waitcnt(0);       // a row has more than 16*NCHD nonzeros in this slab
+    } while (more);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+  }
+  store_pending();
+
+  // A range whose cursor did not stop exactly at its end was not ascending: redo it directly.
+#pragma unroll
+  for (int j = 0; j < RPG; ++j)
+    if (p[j] != p_end[j] && row[j] >= 0) {
+      const int rb = row_offsets[row[j]], re = row_offsets[row[j] + 1];
+      const int b0 = k0 <= 0 ? rb : sd_lower_bound16(column_indices, rb, re, k0, sub, l16, last_nz);
+      int e = k1 >= k ? re : sd_lower_bound16(column_indices, rb, re, k1, sub, l16, last_nz);
+      e = max(e, b0);
+      for (int t = b0; t < e; t += 16)
+        sd_strip_direct_call<float>(n, t, e, l16, L + (size_t)row[j] * n, column_indices, R, out,
+                                    SCALED ? scale : nullptr);
+    }
+}
+
+}  // namespace spdl

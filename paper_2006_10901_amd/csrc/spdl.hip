@@ -12,6 +12,7 @@
 #include "common.hpp"
 #include "csr_softmax.hpp"
 #include "sddmm_group.hpp"
+#include "sddmm_lane.hpp"
 #include "sddmm_mfma.hpp"
 #include "sddmm_nt.hpp"
 #include "sddmm_rowstrip.hpp"
@@ -27,7 +28,7 @@ namespace {
 using namespace spdl;
 
 enum SpmmVariant { kSpmmRowsplit = 0, kSpmmSlab = 1, kSpmmSlabDma = 2, kSpmmMfma = 3, kSpmmVariants };
-enum SddmmVariant { kSddmmRowstrip = 0, kSddmmGroup = 1, kSddmmSlab = 2, kSddmmSlabDma = 3, kSddmmMfma = 4, kSddmmVariants };
+enum SddmmVariant { kSddmmRowstrip = 0, kSddmmGroup = 1, kSddmmSlab = 2, kSddmmSlabDma = 3, kSddmmMfma = 4, kSddmmLane = 5, kSddmmVariants };
 
 std::atomic<int> g_forced[2] = {{-1}, {-1}};
 
@@ -302,6 +303,51 @@ SddmmSlabShape sddmm_slab_shape(int m, int k, int n) {
   return sh;
 }
 
+
+// Launch shape of the lane kernel: sparse rows per 16-lane group (two where A is sparse, so
+// that a stage of arithmetic outlasts the copy of the next slab and R is fetched by fewer
+// workgroups), look-ahead in chunks of 16 column indices (mean + 4 sigma of a row's count in one
+// slab of 128 columns), and the split of A's columns over workgroups that fills the machine.
+struct SddmmLaneShape { int rpg, nchd, ksplit, spp, panels; };
+
+SddmmLaneShape sddmm_lane_shape(int m, int k, int nnz) {
+  SddmmLaneShape sh;
+  const double d = (m > 0 && k > 0) ? (double)nnz / ((double)m * (double)k) : 0.0;
+  const double mean = kLaneS * d, sd = std::sqrt(mean * std::max(0.0, 1.0 - d));
+  sh.nchd = std::max(1, std::min(4, (int)std::ceil((mean + 4.0 * sd + 1.0) / 16.0)));
+  sh.rpg = d >= 0.15 ? 1 : 2;
+  if (sh.rpg == 2 && m <= kSdRows * kComputeUnits / 8) sh.rpg = 1;      // too few rows to share
+  sh.panels = (m + kSdRows * sh.rpg - 1) / (kSdRows * sh.rpg);
+  const int total = std::max(1, (k + kLaneS - 1) / kLaneS);
+  const int want = std::max(1, std::min(total, (kComputeUnits + sh.panels - 1) / sh.panels));
+  sh.spp = (total + want - 1) / want;
+  sh.ksplit = (total + sh.spp - 1) / sh.spp;
+  return sh;
+}
+
+template <int RPG, int NCHD>
+int launch_sddmm_lane(const SddmmLaneShape& sh, int grid, int m, int k, int n, int nnz, const int* ro, const int* ci,
+                      const float* L, const float* R, float* out, const float* scale, hipStream_t st) {
+  static std::atomic<bool> configured{false};
+  const void* plain = reinterpret_cast<const void*>(sddmm_lane_kernel<RPG, NCHD, false>);
+  const void* scaled = reinterpret_cast<const void*>(sddmm_lane_kernel<RPG, NCHD, true>);
+  if (!configured.load()) {
+    for (const void* f : {plain, scaled})
+      if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kLaneLdsBytes) != hipSuccess)
+        return SPDL_ERR_LAUNCH;
+    configured.store(true);
+  }
+  int ksplit = sh.ksplit, spp = sh.spp, panels = sh.panels;
+  void* args[] = {&m, &k, &n, &nnz, &ksplit, &spp, &panels, &ro, &ci, &L, &R, &out, &scale};
+  return hipLaunchKernel(scale ? scaled : plain, dim3(grid), dim3(kSdThreads), args, kLaneLdsBytes, st) == hipSuccess
+             ? SPDL_OK : SPDL_ERR_LAUNCH;
+}
+
+template <typename T>
+bool sddmm_lane_usable(int n, int nnz, const void* L, const void* R) {
+  return sizeof(T) == 4 && sddmm_group_usable<T>(n, L, R) && n <= 128 && nnz < (1 << 29);
+}
+
 template <typename T>
 void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R, spdl_launch_info* info) {
   const bool fast_ok = sddmm_group_usable<T>(n, L, R);
@@ -330,18 +376,33 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
     // banded attention mask leaves most of a panel's column ranges nearly empty)
     const bool worth = n >= 128 || reuse >= 12.0;
     const bool fits = n <= 128 || 128.0 * (double)nnz / ((double)m * (double)k) <= 16.0;
+    // dot products of 65..128 columns: the lane kernel, as long as a panel of 64 rows meets the
+    // same row of R at least once on average
+    const bool lane = sddmm_lane_usable<T>(n, nnz, L, R) && n > 64 && m >= 512 && reuse >= 1.0;
     variant = !fast_ok ? kSddmmRowstrip
+              : lane   ? kSddmmLane
               : (sizeof(T) == 4 && reuse >= 2.0 && worth && m >= 512 && fits && nnz < (1 << 29)) ? kSddmmSlabDma
                                                                                                   : kSddmmGroup;
   }
   if ((variant == kSddmmSlab || variant == kSddmmSlabDma) &&
       !(fast_ok && sizeof(T) == 4 && nnz < (1 << 29) && n < (1 << 21)))   // 32-bit byte offsets
     variant = kSddmmGroup;
+  if (variant == kSddmmLane && !sddmm_lane_usable<T>(n, nnz, L, R)) variant = kSddmmGroup;
   if (variant == kSddmmGroup && !fast_ok) variant = kSddmmRowstrip;
   const int avg = m > 0 ? nnz / m : 0;
   info->variant = variant;
   info->block_threads = 256;
   info->grid_y = 1;
+  if (variant == kSddmmLane) {
+    const SddmmLaneShape sh = sddmm_lane_shape(m, k, nnz);
+    info->vec = 8;
+    info->lanes_per_row = 2;
+    info->rows_per_block = kSdRows * sh.rpg;
+    info->block_threads = kSdThreads;
+    info->grid_x = slab_grid_size(sh.panels, sh.ksplit);
+    info->grid_y = sh.ksplit;               // column ranges of A (the grid is 1-D)
+    return;
+  }
   if (variant == kSddmmSlab || variant == kSddmmSlabDma) {
     const SddmmSlabShape sh = sddmm_slab_shape(m, k, n);
     info->vec = 4 * sh.U;
@@ -426,6 +487,22 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
       }
       sddmm_mfma_kernel<<<dim3(li.grid_x), dim3(256), kSddmmMfmaLdsBytes, st>>>(m, k, n, li.grid_y, ro, ci, L, R, out,
                                                                                 scale);
+      return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
+    } else {
+      return SPDL_ERR_UNSUPPORTED;
+    }
+  }
+  if (li.variant == kSddmmLane) {
+    if constexpr (sizeof(T) == 4) {
+      const SddmmLaneShape sh = sddmm_lane_shape(m, k, nnz);
+      int rc = SPDL_ERR_UNSUPPORTED;
+#define SPDL_LANE(RPG, NCHD)                                                                           \
+  if (sh.rpg == RPG && sh.nchd == NCHD)                                                                \
+    rc = launch_sddmm_lane<RPG, NCHD>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st);
+      SPDL_LANE(1, 1) SPDL_LANE(1, 2) SPDL_LANE(1, 3) SPDL_LANE(1, 4)
+      SPDL_LANE(2, 1) SPDL_LANE(2, 2) SPDL_LANE(2, 3) SPDL_LANE(2, 4)
+#undef SPDL_LANE
+      if (rc != SPDL_OK) return rc;
       return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
     } else {
       return SPDL_ERR_UNSUPPORTED;
@@ -661,7 +738,7 @@ int spdl_force_variant(int op, int variant) {
 
 const char* spdl_variant_name(int op, int variant) {
   static const char* const spmm[] = {"rowsplit", "slab", "slabdma", "mfma"};
-  static const char* const sddmm[] = {"rowstrip", "group", "slab", "slabdma", "mfma"};
+  static const char* const sddmm[] = {"rowstrip", "group", "slab", "slabdma", "mfma", "lane"};
   if (op == 0 && variant >= 0 && variant < kSpmmVariants) return spmm[variant];
   if (op == 1 && variant >= 0 && variant < kSddmmVariants) return sddmm[variant];
   return nullptr;

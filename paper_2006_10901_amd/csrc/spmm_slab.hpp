@@ -122,17 +122,6 @@ __device__ __forceinline__ void slab_fetch(SlabRow& r, int l16, int last_nz, con
   r.a_next = in ? a : 0.f;
 }
 
-// Maximum of two wave-uniform values on the scalar unit (left to itself the compiler moves such
-// a maximum to the vector unit as soon as one of its uses is a vector select).
-__device__ __forceinline__ int scalar_max(int a, int b) {
-  int r;
-  asm("s_max_i32 %0, %1, %2" : "=s"(r) : "s"(a), "s"(b) : "scc");
-  return r;
-}
-
-// Number of leading set bits of a 16-bit piece of a wave mask (scalar arithmetic).
-__device__ __forceinline__ int leading16(unsigned piece) { return __builtin_ctz(~piece | 0x10000u); }
-
 // All of one row's pairs that fall into the slab [slab_start, slab_start + S).
 template <typename T, int S>
 __device__ __forceinline__ void slab_consume(SlabRow& r, float (&acc)[4], const char* buf,

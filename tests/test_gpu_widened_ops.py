@@ -268,7 +268,7 @@ def test_sddmm_scaled_full_size_and_fp16(g, oracle_lib):
     import paper_2006_10901_amd as spdl
     w = wl.lstm(90)
     A, L, R, n = w["A"], w["L"], w["R"], w["n"]
-    assert spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"]) == "slabdma"
+    assert spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"]) == "lane"
     ref, S = oracle_lib.sddmm_scaled(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, L, R)
     g.assert_close(gpu_sddmm_scaled(g, A, L, R, n), ref, S, g.TOL_F32, "lstm-90 scaled sddmm")
     c = wl.conv1x1(True)

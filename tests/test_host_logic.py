@@ -129,8 +129,13 @@ def test_selection_uses_widest_aligned_vector(spdl):
     assert spdl.spdl_select_spmm(64, 64, 128, 100, 4, 4, 0)["vec"] == 1      # misaligned base
     assert spdl.spdl_select_spmm(64, 64, 128, 100, 4, 8, 16)["vec"] == 2
     assert spdl.spdl_select_spmm(64, 64, 3136, 100, 2, 0, 0)["vec"] == 8
-    d = spdl.spdl_select_sddmm(8192, 10240, 128, 8 << 20, 4, 0, 0)
-    assert spdl.spdl_variant_name(1, d["variant"]) == "slabdma" and d["grid_x"] >= 256 and d["grid_y"] == 2
+    d = spdl.spdl_select_sddmm(8192, 10240, 128, 8 << 20, 4, 0, 0)           # 90 % sparse: two rows per lane group
+    assert spdl.spdl_variant_name(1, d["variant"]) == "lane" and d["grid_x"] >= 256 and d["grid_y"] == 4
+    assert d["rows_per_block"] == 128
+    d = spdl.spdl_select_sddmm(8192, 10240, 128, 24 << 20, 4, 0, 0)          # 71 % sparse: one row per lane group
+    assert spdl.spdl_variant_name(1, d["variant"]) == "lane" and d["rows_per_block"] == 64 and d["grid_y"] == 2
+    d = spdl.spdl_select_sddmm(4096, 1024, 4096, 419430, 4, 0, 0)            # wide dot products: slab kernel
+    assert spdl.spdl_variant_name(1, d["variant"]) == "slabdma"
     d = spdl.spdl_select_sddmm(8192, 10240, 130, 8 << 20, 4, 0, 0)           # n % 4 != 0: general kernel
     assert spdl.spdl_variant_name(1, d["variant"]) == "rowstrip" and d["block_threads"] == 256
     d = spdl.spdl_select_sddmm(1024, 1024, 3136, 20000, 2, 0, 0)             # sparse fp16: strip kernel
