@@ -21,6 +21,15 @@
  *   Sizes: m, k, n, nnz >= 0 and m*n, k*n < 2^31.  m == 0, n == 0 and nnz == 0 are valid.
  *   Base pointers must be aligned to their element type; 16-byte aligned bases and n % 4 == 0
  *   (n % 8 == 0 for fp16) select the widest vector path, anything else a narrower one.
+ *   Non-finite inputs.  With finite inputs every result is the definition's.  An Inf or NaN in
+ *   a row of a dense operand reaches the outputs that the definition makes depend on that row
+ *   in every kernel; all SDDMM kernels, the fp32 SpMM kernels and the direct fp16 SpMM kernel
+ *   keep it away from every other output.  The fp16 matrix-core SpMM (chosen when at least one
+ *   position in 32 of A is stored, n % 8 == 0, 16-byte aligned operands) multiplies the zeros of
+ *   its expanded sparse panels by whole rows of B: there a non-finite B[k, j] turns C[i, j] into
+ *   NaN for every row i (other columns of C are not affected).  Callers whose fp16 activations
+ *   can overflow select the direct kernel with spdl_force_variant(0, 0), which follows the
+ *   definition exactly.
  */
 #ifndef SPDL_H_
 #define SPDL_H_
@@ -36,7 +45,8 @@ typedef enum {
   SPDL_ERR_INVALID = -1,      /* negative size, null required pointer, size overflow          */
   SPDL_ERR_LAUNCH = -2,       /* the HIP runtime refused a launch (hipGetLastError != success) */
   SPDL_ERR_BAD_CSR = -3,      /* spdl_validate_csr_host: arrays are not a valid CSR topology   */
-  SPDL_ERR_UNSUPPORTED = -4   /* a forced kernel variant cannot run this problem              */
+  SPDL_ERR_UNSUPPORTED = -4,  /* a forced kernel variant cannot run this problem              */
+  SPDL_ERR_NOMEM = -5         /* a host routine could not allocate its working memory          */
 } spdl_status;
 
 /* SpMM:  C = A B.   (paper Sec. "Sparse Matrix--Matrix Multiplication Operation")
@@ -134,7 +144,8 @@ int spdl_csr_softmax(int m, int nnz, const int* row_offsets, const float* logits
  *     CSR topology of A^T (k x m); inside a row of A^T the entries are in ascending row index
  *     of A (entries of equal row in their stored order).
  *   perm_host : HOST int32[nnz], written: entry t of A^T is entry perm[t] of A.
- *   Returns SPDL_ERR_BAD_CSR when the input is not a valid topology (nothing defined is written). */
+ *   Returns SPDL_ERR_BAD_CSR when the input is not a valid topology (nothing defined is written).
+ *   Allocates nothing. */
 int spdl_build_transpose_host(int m, int k, int nnz, const int* row_offsets_host,
                               const int* column_indices_host, int* t_row_offsets_host,
                               int* t_column_indices_host, int* perm_host);
@@ -148,7 +159,8 @@ int spdl_permute_values(int nnz, int elem_bytes, const int* perm, const void* va
 
 /* Row swizzle (paper Sec. "Row Binning & Row Bundling Heuristics"): row indices sorted by
  * decreasing row length, equal lengths in ascending row index.  Pure host code.
- *   row_offsets_host : HOST int32[m+1];   row_order_host : HOST int32[m], written. */
+ *   row_offsets_host : HOST int32[m+1];   row_order_host : HOST int32[m], written.
+ *   SPDL_ERR_NOMEM if the sort cannot get its merge buffer. */
 int spdl_build_row_order(int m, const int* row_offsets_host, int* row_order_host);
 
 /* Host-side check of a CSR topology: offsets start at 0, never decrease, end at nnz; every
@@ -160,7 +172,10 @@ int spdl_validate_csr_host(int m, int k, int nnz, const int* row_offsets_host,
 
 /* Kernel selection (paper Sec. "Experiments", first paragraph: tile sizes and vector widths
  * are picked from the problem shape).  spdl_select_* report what the dispatcher would launch;
- * spdl_force_variant overrides it for ablation runs (variant < 0 restores the heuristic).
+ * spdl_force_variant overrides it for ablation runs (variant < 0 restores the heuristic); a
+ * forced variant that cannot run the problem at hand falls back to one that can.  The override
+ * is one process-wide setting per operation, read by every later call on any thread: it is not
+ * meant to be changed while other threads are inside the library.
  * The variant ids are listed by spdl_variant_name. */
 typedef struct {
   int variant;          /* kernel family id                                        */

@@ -114,7 +114,7 @@ __global__ __launch_bounds__(256) void sddmm_mfma_kernel(
       const unsigned off = voff[j] + (in ? (unsigned)vpiece[j] * 16u : 0u);     // past n: the stage's first piece
       const unsigned m0v = dst + (unsigned)j * 1024u;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                   :: "s"(m0v), "v"(off), "s"(base) : "memory");
+                   :: "s"(m0v), "v"(off), "s"(base) : "memory", "m0");
     }
   };
 

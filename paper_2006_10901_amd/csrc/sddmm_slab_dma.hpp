@@ -80,7 +80,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_dma_kernel(
       const unsigned voff = (last ? row_off_last[i] : row_off[i]) + col_off;
       const unsigned m0v = dst + (unsigned)i * (16u * 1024u);
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                   :: "s"(m0v), "v"(voff), "s"(base) : "memory");
+                   :: "s"(m0v), "v"(voff), "s"(base) : "memory", "m0");
     }
   };
 

@@ -132,12 +132,33 @@ constexpr int kSpmmMfmaKParts = 2;                // waves per tile, splitting t
 // when at least one position in 32 is stored.
 inline bool mfma_dense_enough(int m, int k, int nnz) { return 32.0 * (double)nnz >= (double)m * (double)k; }
 
+// The matrix-core SpMM keeps rows of B in registers whose loads are still in flight (explicit
+// waits); a register spilled inside that window would be copied before its data has arrived.
+// The kernel is built without spills; should a toolchain ever produce one (private memory per
+// lane != 0), the variant is not offered and the row-splitting kernel runs instead.  Queried
+// once; without a device (selection queries on a CPU-only host) the answer is yes.
+bool spmm_mfma_runnable() {
+  static const bool ok = [] {
+    hipFuncAttributes attr;
+    bool fine = true;
+    for (const void* f : {reinterpret_cast<const void*>(spmm_mfma_kernel<kSpmmMfmaWaves, kSpmmMfmaKParts, int, 1>),
+                          reinterpret_cast<const void*>(spmm_mfma_kernel<kSpmmMfmaWaves, kSpmmMfmaKParts, int16_t, 1>)})
+      if (hipFuncGetAttributes(&attr, f) == hipSuccess && attr.localSizeBytes != 0) fine = false;
+    (void)hipGetLastError();
+    return fine;
+  }();
+  return ok;
+}
+
 template <typename T>
 void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, spdl_launch_info* info) {
   int variant = g_forced[0].load();
   const bool mfma_ok = sizeof(T) == 2 && n % 8 == 0 && n < (1 << 24) && k >= 16 && aligned(B, 16) && aligned(C, 16);
-  if (variant == kSpmmMfma && (!mfma_ok || nnz == 0)) variant = kSpmmRowsplit;   // nnz == 0: B may be null
-  if (variant < 0 && mfma_ok && mfma_dense_enough(m, k, nnz)) variant = kSpmmMfma;
+  // nnz == 0: column_indices, values and B may be null, and the slab and matrix-core kernels
+  // fetch from them unconditionally; the row-splitting kernel only writes the zeros of C
+  if (nnz == 0 && (variant == kSpmmMfma || variant == kSpmmSlab || variant == kSpmmSlabDma)) variant = kSpmmRowsplit;
+  if (variant == kSpmmMfma && (!mfma_ok || !spmm_mfma_runnable())) variant = kSpmmRowsplit;
+  if (variant < 0 && mfma_ok && nnz > 0 && mfma_dense_enough(m, k, nnz) && spmm_mfma_runnable()) variant = kSpmmMfma;
   if (variant == kSpmmMfma) {
     // 32-row panels, kSpmmMfmaWaves tiles per workgroup.  (64-row panels, which would halve the
     // reads of B, need 256 accumulator registers per lane; the compiler then spills in the main
@@ -611,13 +632,16 @@ int spdl_build_transpose_host(int m, int k, int nnz, const int* ro, const int* c
     }
   }
   for (int c = 0; c < k; ++c) t_ro[c + 1] += t_ro[c];
-  std::vector<int> cursor(t_ro, t_ro + k);
+  // The write cursors live in t_ro itself (no allocation): entry c is advanced as column c fills
+  // and ends at the start of column c+1, so shifting the array up by one restores the offsets.
   for (int i = 0; i < m; ++i)
     for (int p = ro[i]; p < ro[i + 1]; ++p) {
-      const int t = cursor[ci[p]]++;
+      const int t = t_ro[ci[p]]++;
       t_ci[t] = i;
       perm[t] = p;
     }
+  for (int c = k; c > 0; --c) t_ro[c] = t_ro[c - 1];
+  t_ro[0] = 0;
   return SPDL_OK;
 }
 
@@ -691,9 +715,13 @@ int spdl_sddmm_f16(int m, int k, int n, int nnz, const int* row_offsets, const i
 int spdl_build_row_order(int m, const int* row_offsets_host, int* row_order_host) {
   if (m < 0 || (m > 0 && (!row_offsets_host || !row_order_host))) return SPDL_ERR_INVALID;
   std::iota(row_order_host, row_order_host + m, 0);
-  std::stable_sort(row_order_host, row_order_host + m, [&](int a, int b) {
-    return row_offsets_host[a + 1] - row_offsets_host[a] > row_offsets_host[b + 1] - row_offsets_host[b];
-  });
+  try {                                   // std::stable_sort allocates a merge buffer
+    std::stable_sort(row_order_host, row_order_host + m, [&](int a, int b) {
+      return row_offsets_host[a + 1] - row_offsets_host[a] > row_offsets_host[b + 1] - row_offsets_host[b];
+    });
+  } catch (...) {
+    return SPDL_ERR_NOMEM;
+  }
   return SPDL_OK;
 }
 
@@ -751,10 +779,11 @@ const char* spdl_status_string(int status) {
     case SPDL_ERR_LAUNCH: return "kernel launch failed";
     case SPDL_ERR_BAD_CSR: return "not a valid CSR topology";
     case SPDL_ERR_UNSUPPORTED: return "variant does not support this problem";
+    case SPDL_ERR_NOMEM: return "host allocation failed";
     default: return "unknown status";
   }
 }
 
-int spdl_version(void) { return 110; }
+int spdl_version(void) { return 120; }
 
 }  // extern "C"

@@ -42,6 +42,20 @@ def test_config1_tiny(g, oracle_lib):
     sddmm_case(g, oracle_lib, A, w["L"], w["R"], w["n"], g.TOL_F32, "cfg1 sddmm")
 
 
+def test_row_order_built_by_the_library_feeds_the_kernels(g, oracle_lib):
+    """The host routine's own output (not the oracle's) as row_order, on skewed rows where the
+    order matters for balance: same bits as with the identity order, and equal to the oracle's
+    order array."""
+    import paper_2006_10901_amd as spdl
+    A = wl.lognormal_rows_csr(700, 900, 0.08, 77)
+    B = wl.dense(A.k, 128, 78)
+    mine = spdl.spdl_build_row_order(A.m, A.row_offsets)
+    assert np.array_equal(mine, oracle_lib.row_order(A.m, A.row_offsets))
+    _, c_mine = spmm_case(g, oracle_lib, A, B, 128, g.TOL_F32, mine, "spmm with the library's row order")
+    _, c_ident = spmm_case(g, oracle_lib, A, B, 128, g.TOL_F32, None, "spmm identity order")
+    assert np.array_equal(c_mine, c_ident)
+
+
 def test_identity_and_permutation_return_rows_of_B_exactly(g, oracle_lib):
     m, n = 300, 128
     B = wl.dense(m, n, 3)

@@ -149,6 +149,31 @@ def test_selection_uses_widest_aligned_vector(spdl):
     assert spdl.spdl_variant_name(0, 0) is not None and spdl.spdl_variant_name(0, 99) is None
 
 
+def test_forced_slab_variants_never_run_an_empty_matrix(spdl):
+    """With nnz == 0 the sparse arrays and B may be null; the kernels that fetch from them
+    unconditionally must not be chosen, forced or not."""
+    try:
+        for forced in (1, 2, 3):
+            spdl.spdl_force_variant(0, forced)
+            for eb in (4, 2):
+                s = spdl.spdl_select_spmm(4096, 4096, 128, 0, eb, 0, 0)
+                assert spdl.spdl_variant_name(0, s["variant"]) == "rowsplit", (forced, eb)
+            s = spdl.spdl_select_spmm(4096, 4096, 128, 1 << 20, 4, 0, 0)
+            if forced in (1, 2):
+                assert s["variant"] == forced
+    finally:
+        spdl.spdl_force_variant(0, -1)
+
+
+def test_status_strings(spdl):
+    lib = ctypes.CDLL(spdl.LIB_PATH)
+    lib.spdl_status_string.restype = ctypes.c_char_p
+    seen = {lib.spdl_status_string(c).decode() for c in (0, -1, -2, -3, -4, -5)}
+    assert len(seen) == 6 and "unknown status" not in seen
+    assert lib.spdl_status_string(-99).decode() == "unknown status"
+    assert lib.spdl_version() >= 120
+
+
 def test_workload_statistics():
     A = wl.tiny()["A"]
     assert A.m == 512 and abs(A.nnz / 512 / 512 - 0.10) < 0.01
