@@ -29,13 +29,27 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 
 
-# HBM bytes per launch (read + written) of each kernel family on this workload, from the two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarised in profiles/lstm_sweep_hbm_traffic.md,
-# scaled by the copy-kernel factors given there.  Counters cannot be read from inside this
-# process, so the figures are carried here and refreshed whenever the kernels change.
-MEASURED_HBM_TRAFFIC_BYTES = {
-    "spmm_slabdma": 159.9e6, "sddmm_slabdma": 176.0e6, "spmm_rowsplit": 89.2e6, "sddmm_group": 268.4e6,
-}
+TRAFFIC_PROFILE = os.path.join("profiles", "lstm_sweep_hbm_traffic.md")
+
+
+def measured_hbm_traffic():
+    """HBM bytes per launch (read + written) of each kernel family on the LSTM sweep, from the two
+    rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarised in profiles/lstm_sweep_hbm_traffic.md
+    (already scaled by the copy-kernel factors given there).  Hardware counters cannot be read
+    from inside this process, so the figure reported as roofline.traffic is the one of that
+    summary, refreshed whenever the kernels change; the JSON says where it comes from."""
+    out = {}
+    path = os.path.join(ROOT, TRAFFIC_PROFILE)
+    if not os.path.exists(path):
+        return out
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 7 and cells[0] and cells[0] != "kernel" and not set(cells[0]) <= set("-: "):
+            try:
+                out[cells[0]] = (float(cells[4]) + float(cells[5])) * 1e6
+            except ValueError:
+                pass
+    return out
 
 
 def spmm_bytes(m, k, n, nnz, eb=4):
@@ -160,7 +174,71 @@ def widened_cases(wl, spdl, torch):
         spdl.spdl_spmm(F.k, F.m, 4096, F.nnz, tro, tci, tval, torder, tB, tC)
     out.append(WidenedCase("ffn_W1_transposed", "permute+spmm", spdl.spdl_variant_name(0, info["variant"]), F.nnz,
                            transposed, spmm_bytes(F.k, F.m, 4096, F.nnz) + 12 * F.nnz, 2.0 * F.nnz * 4096))
+    # SDDMM with the right-hand operand not transposed (n x k), on the LSTM topology at 90 %
+    w = wl.lstm(90, with_dense=False)
+    N = w["A"]
+    nro, nci = dev(N.row_offsets), dev(N.column_indices)
+    nL = torch.randn((N.m, 128), device="cuda")
+    nRn = torch.randn((128, N.k), device="cuda")
+    nout = torch.empty(N.nnz, device="cuda")
+    out.append(WidenedCase("lstm90_rhs_not_transposed", "sddmm_nt", "lane_per_entry", N.nnz,
+                           lambda: spdl.spdl_sddmm_nt(N.m, N.k, 128, N.nnz, nro, nci, None, nL, nRn, nout),
+                           sddmm_bytes(N.m, N.k, 128, N.nnz), 2.0 * N.nnz * 128, dims=(N.m, N.k, 128)))
     return out
+
+
+EXTRA_GROUPS = ("ffn", "attention", "conv_f16", "conv_f32", "imbalance", "widened")
+
+
+def extra_cases(groups, wl, spdl, torch):
+    """The configurations outside the timed step, by group name (also selectable with --only for
+    profiling runs)."""
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    extra = []
+    if "ffn" in groups:                     # Transformer feed-forward layer, 4096 tokens
+        for which in (1, 2):
+            w = wl.transformer_ffn(which)
+            extra.append(Case(f"ffn_W{which}", "spmm", w["A"], 4096, (w["B"],), spdl, torch))
+            extra.append(Case(f"ffn_W{which}", "sddmm", w["A"], 4096, (w["L"], w["R"]), spdl, torch))
+    if "attention" in groups:               # one head of the banded sparse attention
+        w = wl.attention(0)
+        extra.append(Case("attention_head", "sddmm", w["A"], 64, (w["Q"], w["K"]), spdl, torch))
+        extra.append(Case("attention_head", "spmm", w["A"], 64, (w["V"],), spdl, torch))
+    if "conv_f16" in groups:                # sparse 1x1 convolution, fp16 in / fp32 accumulate
+        for skew in (False, True):
+            w = wl.conv1x1(skew)
+            nm = "conv1x1_f16_skewed" if skew else "conv1x1_f16"
+            extra.append(Case(nm, "spmm", w["A"], 3136, (w["B"],), spdl, torch, f16=True))
+            extra.append(Case(nm, "sddmm", w["A"], 3136, (w["L"], w["R"]), spdl, torch, f16=True))
+    if "conv_f32" in groups:                # the same two topologies in fp32 (row-length skew without matrix cores)
+        for skew in (False, True):
+            w = wl.conv1x1(skew)
+            A = w["A"]
+            A32 = wl.Csr(A.m, A.k, A.row_offsets, A.column_indices, A.values.astype(np.float32))
+            nm = "conv1x1_f32_skewed" if skew else "conv1x1_f32"
+            f32 = lambda a: a.astype(np.float32)
+            extra.append(Case(nm, "spmm", A32, 3136, (f32(w["B"]),), spdl, torch))
+            extra.append(Case(nm, "sddmm", A32, 3136, (f32(w["L"]), f32(w["R"])), spdl, torch))
+    if "imbalance" in groups:
+        # Load imbalance (the paper's load-imbalance figure): 8192 x 2048 at 75 % sparsity, n = 128,
+        # equal row lengths against gamma-distributed ones (coefficient of variation about 1),
+        # each with the row order sorted by length and with no row order.
+        for cov in (0.0, 1.0):
+            w = wl.imbalance_sweep(cov)
+            A = w["A"]
+            lens = A.row_lengths
+            tag = f"imbalance_cov{lens.std() / max(lens.mean(), 1e-9):.2f}"
+            sorted_case = Case(tag + "_sorted_order", "spmm", A, 128, (w["B"],), spdl, torch)
+            extra.append(sorted_case)
+            ro, ci, val, B = dev(A.row_offsets), dev(A.column_indices), dev(A.values), dev(w["B"])
+            C = torch.empty((A.m, 128), device="cuda")
+            extra.append(WidenedCase(tag + "_natural_order", "spmm", sorted_case.kernel, A.nnz,
+                                     lambda A=A, ro=ro, ci=ci, val=val, B=B, C=C:
+                                     spdl.spdl_spmm(A.m, A.k, 128, A.nnz, ro, ci, val, None, B, C),
+                                     spmm_bytes(A.m, A.k, 128, A.nnz), 2.0 * A.nnz * 128, dims=(A.m, A.k, 128)))
+    if "widened" in groups:
+        extra += widened_cases(wl, spdl, torch)
+    return extra
 
 
 def time_cases(cases, steps, warmup, torch):
@@ -252,7 +330,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-extra", action="store_true", help="skip the Transformer/attention/conv report")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default="", help="comma list of LSTM sparsities to run (profiling aid)")
+    ap.add_argument("--only", default="",
+                    help="profiling aid: comma list of LSTM sparsities and/or groups of the other configurations ("
+                         + ", ".join(EXTRA_GROUPS) + ") to run in the timed loop instead of the full step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 256 MiB device copies (reference dispatches for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -266,7 +346,12 @@ def main():
         sys.exit("bench.py needs a GPU")
     spdl.lib()
 
-    sparsities = [int(s) for s in args.only.split(",")] if args.only else list(wl.LSTM_SPARSITIES)
+    tokens = [t for t in args.only.split(",") if t]
+    only_groups = [t for t in tokens if t in EXTRA_GROUPS]
+    bad = [t for t in tokens if t not in EXTRA_GROUPS and not t.isdigit()]
+    if bad:
+        sys.exit(f"bench.py: --only does not know {bad}")
+    sparsities = [int(t) for t in tokens if t.isdigit()] if tokens else list(wl.LSTM_SPARSITIES)
     cases, lstm90 = [], None
     for sp in sparsities:
         t0 = time.time()
@@ -276,6 +361,10 @@ def main():
         cases.append(Case(f"lstm{sp}", "spmm", w["A"], 128, (w["B"],), spdl, torch))
         cases.append(Case(f"lstm{sp}", "sddmm", w["A"], 128, (w["L"], w["R"]), spdl, torch))
         log(f"[bench] lstm {sp}%: nnz={w['A'].nnz} generated+uploaded in {time.time() - t0:.1f}s")
+
+    if only_groups:
+        cases += extra_cases(only_groups, wl, spdl, torch)
+        args.no_extra = True
 
     if args.copy_calibration:
         # a plain copy kernel of known size: 256 MiB read + 256 MiB written per dispatch
@@ -302,7 +391,9 @@ def main():
     roofline = {
         "bound": "alu", "achieved": round(achieved, 3), "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
         "frac": round(achieved / FP32_VECTOR_PEAK_TFLOPS, 4),
-        "traffic": MEASURED_HBM_TRAFFIC_BYTES.get(f"{dom_op}_{dom_kernel}"),
+        "traffic": measured_hbm_traffic().get(f"{dom_op}_{dom_kernel}"),
+        "traffic_source": TRAFFIC_PROFILE + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, per dispatch)",
+        "traffic_measured_in_run": False,
         "algorithmic_bytes_per_launch": dom["bytes"] / dom["launches"],
         "kernel": f"{dom_op}_{dom_kernel}", "avg_launch_us": round(dom["ms"] / dom["launches"] * 1e3, 2),
         "flops_per_launch": dom["flops"] / dom["launches"],
@@ -327,23 +418,10 @@ def main():
         result["one_off_host_costs"] = one_off_host_costs(wl, spdl, lstm90)
 
     if not args.no_extra:
-        extra = []
-        for which in (1, 2):
-            w = wl.transformer_ffn(which)
-            extra.append(Case(f"ffn_W{which}", "spmm", w["A"], 4096, (w["B"],), spdl, torch))
-            extra.append(Case(f"ffn_W{which}", "sddmm", w["A"], 4096, (w["L"], w["R"]), spdl, torch))
-        w = wl.attention(0)
-        extra.append(Case("attention_head", "sddmm", w["A"], 64, (w["Q"], w["K"]), spdl, torch))
-        extra.append(Case("attention_head", "spmm", w["A"], 64, (w["V"],), spdl, torch))
-        for skew in (False, True):
-            w = wl.conv1x1(skew)
-            nm = "conv1x1_f16_skewed" if skew else "conv1x1_f16"
-            extra.append(Case(nm, "spmm", w["A"], 3136, (w["B"],), spdl, torch, f16=True))
-            extra.append(Case(nm, "sddmm", w["A"], 3136, (w["L"], w["R"]), spdl, torch, f16=True))
-        extra += widened_cases(wl, spdl, torch)
+        extra = extra_cases(EXTRA_GROUPS, wl, spdl, torch)
         time_cases(extra, max(5, args.steps // 2), 2, torch)
         result["other_configs"] = [c.report() for c in extra]
-        ffn = [c for c in extra if c.name.startswith("ffn")]
+        ffn = [c for c in extra if c.name.startswith("ffn_W") and c.op in ("spmm", "sddmm")]
         t = sum(float(np.mean(c.ms)) for c in ffn) * 1e-3
         result["transformer_ffn_gflops"] = round(sum(c.flops for c in ffn) / t / 1e9, 1)
 

@@ -174,6 +174,21 @@ def test_status_strings(spdl):
     assert lib.spdl_version() >= 120
 
 
+def test_bench_reads_its_traffic_figures_from_the_profile_summary():
+    """roofline.traffic is not a constant of bench.py: it is the read + written MB of the kernel's
+    row in profiles/lstm_sweep_hbm_traffic.md."""
+    import bench
+    table = bench.measured_hbm_traffic()
+    assert table, "no kernel rows parsed from the profile summary"
+    text = open(os.path.join(ROOT, bench.TRAFFIC_PROFILE)).read()
+    for name, nbytes in table.items():
+        row = [l for l in text.splitlines() if l.startswith("| " + name + " ")]
+        assert len(row) == 1
+        cells = [c.strip() for c in row[0].strip("|").split("|")]
+        assert abs(nbytes - (float(cells[4]) + float(cells[5])) * 1e6) < 1.0
+        assert nbytes > 1e6
+
+
 def test_workload_statistics():
     A = wl.tiny()["A"]
     assert A.m == 512 and abs(A.nnz / 512 / 512 - 0.10) < 0.01
