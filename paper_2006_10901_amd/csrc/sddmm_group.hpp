@@ -48,13 +48,18 @@ __device__ __forceinline__ float reduce16x16(float (&x)[16], int l16) {
 
 // Dot products of one strip of up to 16 consecutive nonzeros [q, q+16) ∩ [q, end) of `row`,
 // rows of L and R gathered straight from global memory.  Called by all 16 lanes of a group.
+// The element offset in R of the row that lane l16 of a group gathers for the strip [q, q+16) of a
+// sparse row ending at `end`: its own nonzero's column, past the end the last entry's again.
+__device__ __forceinline__ int sddmm_strip_offset(int n, int q, int end, int l16,
+                                                  const int* __restrict__ column_indices) {
+  return column_indices[min(q + l16, end - 1)] * n;
+}
+
 template <typename T>
-__device__ __forceinline__ void sddmm_strip_direct(int n, int q, int end, int l16, const T* __restrict__ Lrow,
-                                                   const int* __restrict__ column_indices,
-                                                   const T* __restrict__ R, T* __restrict__ out,
-                                                   const T* __restrict__ scale = nullptr) {
+__device__ __forceinline__ void sddmm_strip_direct_at(int n, int q, int end, int l16, int roff,
+                                                      const T* __restrict__ Lrow, const T* __restrict__ R,
+                                                      T* __restrict__ out, const T* __restrict__ scale = nullptr) {
   const int cidx = q + l16;
-  const int roff = column_indices[min(cidx, end - 1)] * n;     // past the end: last entry again
   float partial[16];
 #pragma unroll
   for (int t = 0; t < 16; ++t) partial[t] = 0.f;
@@ -84,6 +89,14 @@ __device__ __forceinline__ void sddmm_strip_direct(int n, int q, int end, int l1
   }
   const float total = reduce16x16(partial, l16);
   if (cidx < end) sddmm_store<T>(out, scale, cidx, total);
+}
+
+template <typename T>
+__device__ __forceinline__ void sddmm_strip_direct(int n, int q, int end, int l16, const T* __restrict__ Lrow,
+                                                   const int* __restrict__ column_indices,
+                                                   const T* __restrict__ R, T* __restrict__ out,
+                                                   const T* __restrict__ scale = nullptr) {
+  sddmm_strip_direct_at<T>(n, q, end, l16, sddmm_strip_offset(n, q, end, l16, column_indices), Lrow, R, out, scale);
 }
 
 // Work is split by nonzeros, not by rows: every wave owns `per_wave` consecutive entries of
@@ -121,34 +134,47 @@ __global__ __launch_bounds__(256) void sddmm_group_kernel(
   }
   int row = lo;
   int row_end = row_offsets[row + 1];
-  while (p < range_end) {
+  // The walk runs one round ahead of the arithmetic: the column indices of the next round's strips
+  // are requested before the current round's gathers are waited for, so a round costs one memory
+  // latency (the rows of R), not two in a row (indices, then rows).
+  int cur_row = 0, cur_q = 0, cur_end = 0, cur_off = 0;
+  bool have = false;
+  while (true) {
     int my_row = 0, my_q = 0, my_end = 0;
-    while (row_end <= p) {                     // p reached the end of this row: next non-empty row
-      ++row;
-      row_end = row_offsets[row + 1];
-    }
-    const int seg_end = min(row_end, range_end);
-    if (p + 64 <= seg_end) {                   // four full strips of the same row
-      my_row = row;
-      my_q = p + 16 * sub;
-      my_end = seg_end;
-      p += 64;
-    } else {
+    const bool next = p < range_end;
+    if (next) {
+      while (row_end <= p) {                     // p reached the end of this row: next non-empty row
+        ++row;
+        row_end = row_offsets[row + 1];
+      }
+      const int seg_end = min(row_end, range_end);
+      if (p + 64 <= seg_end) {                   // four full strips of the same row
+        my_row = row;
+        my_q = p + 16 * sub;
+        my_end = seg_end;
+        p += 64;
+      } else {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        if (p < range_end) {
-          while (row_end <= p) {
-            ++row;
-            row_end = row_offsets[row + 1];
+        for (int g = 0; g < 4; ++g) {
+          if (p < range_end) {
+            while (row_end <= p) {
+              ++row;
+              row_end = row_offsets[row + 1];
+            }
+            const int e = min(row_end, range_end);
+            if (sub == g) { my_row = row; my_q = p; my_end = e; }
+            p = min(p + 16, e);
           }
-          const int e = min(row_end, range_end);
-          if (sub == g) { my_row = row; my_q = p; my_end = e; }
-          p = min(p + 16, e);
         }
       }
     }
-    if (my_q < my_end)
-      sddmm_strip_direct<T>(n, my_q, my_end, l16, L + (size_t)my_row * n, column_indices, R, out, scale);
+    int my_off = 0;
+    if (my_q < my_end) my_off = sddmm_strip_offset(n, my_q, my_end, l16, column_indices);
+    if (have && cur_q < cur_end)
+      sddmm_strip_direct_at<T>(n, cur_q, cur_end, l16, cur_off, L + (size_t)cur_row * n, R, out, scale);
+    if (!next) break;
+    cur_row = my_row; cur_q = my_q; cur_end = my_end; cur_off = my_off;
+    have = true;
   }
 }
 

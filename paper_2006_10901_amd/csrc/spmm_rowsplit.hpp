@@ -43,18 +43,32 @@ __global__ __launch_bounds__(256) void spmm_rowsplit_kernel(
   for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
 
   int p = start + seg * U;
-  for (; p + U <= end; p += SEG * U) {
-    float a[U];
-    int c[U];
-    float b[U][VEC];
+  // Full batches of U nonzeros.  The values and column indices of the next batch are requested
+  // before the gathers of the current one are waited for, so a batch costs one memory latency
+  // (the rows of B), not two in a row (indices, then rows).
+  float a[U];
+  int c[U];
+  if (p + U <= end) {
 #pragma unroll
     for (int u = 0; u < U; ++u) { a[u] = (float)values[p + u]; c[u] = (int)column_indices[p + u]; }
+  }
+  for (; p + U <= end; p += SEG * U) {
+    float b[U][VEC];
 #pragma unroll
     for (int u = 0; u < U; ++u) Pack<T, VEC>::load(Bcol + (size_t)c[u] * n, b[u]);
+    float an[U];
+    int cn[U];
+    const int pn = p + SEG * U;
+    if (pn + U <= end) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) { an[u] = (float)values[pn + u]; cn[u] = (int)column_indices[pn + u]; }
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int v = 0; v < VEC; ++v) acc[v] = __builtin_fmaf(a[u], b[u][v], acc[v]);
+#pragma unroll
+    for (int u = 0; u < U; ++u) { a[u] = an[u]; c[u] = cn[u]; }
   }
   // after the full batches, p is the start of this group's next batch: past the row end for every
   // group but the one that owns the short last batch
