@@ -18,6 +18,23 @@ HIP_FLAGS = [
 ]
 
 
+MICROBENCH_SRC = os.path.join(_HERE, "microbench", "inner_loop_rates.hip")
+MICROBENCH_BIN = os.path.join(_HERE, "microbench", "inner_loop_rates")
+
+
+def build_microbench(verbose: bool = False) -> str:
+    """The stand-alone program that measures the issue rates bounding the kernels' inner loops
+    (run it on the GPU machine: paper_2006_10901_amd/microbench/inner_loop_rates)."""
+    flags = [f for f in HIP_FLAGS if f not in ("-fPIC", "-shared")]
+    cmd = [HIPCC, *flags, "-o", MICROBENCH_BIN, MICROBENCH_SRC]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + proc.stdout)
+    return MICROBENCH_BIN
+
+
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
@@ -34,3 +51,4 @@ def build(verbose: bool = False) -> str:
 
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_microbench(verbose=True))

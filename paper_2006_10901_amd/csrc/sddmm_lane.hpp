@@ -65,7 +65,7 @@ __device__ __forceinline__ int group_sum16(int v) {
 // Value of lane Q of each quad, in all four lanes of the quad.
 template <int Q>
 __device__ __forceinline__ int quad_bcast(int v) {
-  return __builtin_amdgcn_update_dpp(0, v, Q * 0x55 /* quad_perm [Q,Q,Q,Q] */, 0xf, 0xf, false);
+  return __builtin_amdgcn_mov_dpp(v, Q * 0x55 /* quad_perm [Q,Q,Q,Q] */, 0xf, 0xf, false);
 }
 
 // Sum of a over the four lanes of a quad, in every lane.
@@ -177,10 +177,11 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
         lr[j][8 * s + 4 * u + 3] = in ? vv.w : 0.f;
       }
   }
-  // byte offset of step s inside this lane's 256-byte row (the region is added to the row base)
+  // byte offset of step s from the start of an R row in region 0: this lane's region, its half of
+  // the 256-byte row, and the rotated 32-byte piece
   int x[4];
 #pragma unroll
-  for (int s = 0; s < 4; ++s) x[s] = (h4 & 1) * 128 + ((t4 - s) & 3) * 32;
+  for (int s = 0; s < 4; ++s) x[s] = (h4 >> 1) * kLaneRegion + (h4 & 1) * 128 + ((t4 - s) & 3) * 32;
 
   // Look-ahead of row j from position `from`: the next 16*NCHD column indices, lane 4t+h of the
   // group holding index 16 i + 4 h + t of chunk i; with them the values of A if the results are
@@ -239,8 +240,8 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
   for (int s = 0; s < nslabs; ++s) {
     const int slab_start = k0 + s * S;
     const int buf_off = (s & 1) * kLaneBuf;
-    // LDS byte offset of R row c in this lane's region = (c << 8) + row_base
-    const int row_base = buf_off + (h4 >> 1) * kLaneRegion - slab_start * 256;
+    // LDS byte offset of R row c in region 0 = (c << 8) + row_base
+    const int row_base = buf_off - slab_start * 256;
     bool first = true, more;
     do {
       // A use of every look-ahead register before the copies are issued: the compiler places its
@@ -291,10 +292,12 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
         vl[j] = used - t4;       // this quad's nonzero of strip q of chunk i exists if vl > 16 i + 4 q
         st_off[j] = (p[j] + perm) << 2;
         p[j] += used;
-        // the column indices are moved out of the way of the next look-ahead
+        // LDS offsets of this lane's own nonzero of every chunk (the first row of the slab if it
+        // does not exist); the strips broadcast them inside the quads.  This also moves the
+        // indices out of the way of the next look-ahead.
 #pragma unroll
         for (int i = 0; i < NCHD; ++i) {
-          col[j][i] = cn[j][i];
+          col[j][i] = __builtin_amdgcn_inverse_ballot_w64(okm[j][i]) ? (cn[j][i] << 8) + row_base : buf_off;
           if (SCALED) scv[j][i] = sc[j][i];
         }
         fetch(j, p[j]);
@@ -305,14 +308,12 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
         // multiply-adds, also across strips, through two register sets used in turn; reads
         // for a strip that does not exist hit a valid address and are dropped.
         auto strip_off = [&](int i, int q) -> int {
-          int c;
           switch (q) {
-            case 0: c = quad_bcast<0>(col[j][i]); break;
-            case 1: c = quad_bcast<1>(col[j][i]); break;
-            case 2: c = quad_bcast<2>(col[j][i]); break;
-            default: c = quad_bcast<3>(col[j][i]); break;
+            case 0: return quad_bcast<0>(col[j][i]);
+            case 1: return quad_bcast<1>(col[j][i]);
+            case 2: return quad_bcast<2>(col[j][i]);
+            default: return quad_bcast<3>(col[j][i]);
           }
-          return vl[j] > 16 * i + 4 * q ? (c << 8) + row_base : buf_off;
         };
         f32x4 b[2][2];
         int off = strip_off(0, 0);
