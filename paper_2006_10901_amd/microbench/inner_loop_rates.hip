@@ -154,6 +154,43 @@ __global__ __launch_bounds__(1024) void sddmm_lane_step(float* out, int iters, c
   out[blockIdx.x * 1024 + threadIdx.x] = tot;
 }
 
+// SpMM, four lanes per nonzero (lane 4t+h: every fourth nonzero of the strip, columns 16h..16h+15
+// of a 64-column tile): the nonzero's value and LDS offset are broadcast inside the quad, its 64
+// bytes of the B row are read as four 16-byte pieces in an order rotated by t (conflict-free
+// whatever the rows), and sixteen plain multiply-adds accumulate them.
+__global__ __launch_bounds__(1024) void spmm_lane_step(float* out, int iters, const int* __restrict__ rows, int nrows) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  for (int i = threadIdx.x; i < nrows * 64; i += 1024) reinterpret_cast<float*>(lds)[i] = (float)(i & 7);
+  __syncthreads();
+  const int l16 = threadIdx.x & 15, t4 = l16 >> 2, h4 = l16 & 3;
+  int x[4];
+  for (int r = 0; r < 4; ++r) x[r] = h4 * 64 + ((r + t4) & 3) * 16;
+  float acc[16];
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+  const int* myrows = rows + threadIdx.x;
+  for (int it = 0; it < iters; ++it) {
+    const int off_own = myrows[(it & 15) * 1024] % nrows * 256;      // this lane's own nonzero of the chunk
+    const float a_own = 0.5f + off_own;
+#define SPMM_LANE_STRIP(Q)                                                                          \
+    {                                                                                               \
+      const int off = __builtin_amdgcn_mov_dpp(off_own, (Q) * 0x55, 0xf, 0xf, false);               \
+      const float a = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, a_own), (Q) * 0x55, 0xf, 0xf, false)); \
+      _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                               \
+        const f32x4 b = *reinterpret_cast<const f32x4*>(lds + off + x[r]);                          \
+        acc[4 * r + 0] = __builtin_fmaf(a, b.x, acc[4 * r + 0]);                                    \
+        acc[4 * r + 1] = __builtin_fmaf(a, b.y, acc[4 * r + 1]);                                    \
+        acc[4 * r + 2] = __builtin_fmaf(a, b.z, acc[4 * r + 2]);                                    \
+        acc[4 * r + 3] = __builtin_fmaf(a, b.w, acc[4 * r + 3]);                                    \
+      }                                                                                             \
+    }
+    SPMM_LANE_STRIP(0) SPMM_LANE_STRIP(1) SPMM_LANE_STRIP(2) SPMM_LANE_STRIP(3)
+#undef SPMM_LANE_STRIP
+  }
+  float tot = 0.f;
+  for (int i = 0; i < 16; ++i) tot += acc[i];
+  out[blockIdx.x * 1024 + threadIdx.x] = tot;
+}
+
 template <typename F> float best_ms(F f) {
   hipEvent_t a, b;
   (void)hipEventCreate(&a); (void)hipEventCreate(&b);
@@ -209,6 +246,10 @@ int main() {
   { float ms = best_ms([&] { sddmm_lane_step<<<CU, 1024, 2 * (128 * 256 + 16)>>>(out, iters, rows, 128); });
     printf("SDDMM step, 4 lanes per nonzero (1 address, 2 reads, 8 plain multiply-adds per step): %6.1f FMA/clk/CU\n",
            per_cu_clk((double)CU * 1024 * iters * 4 * 32, ms)); }
+  CK(hipFuncSetAttribute((const void*)spmm_lane_step, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+  { float ms = best_ms([&] { spmm_lane_step<<<CU, 1024, 448 * 256>>>(out, iters, rows, 448); });
+    printf("SpMM step, 4 lanes per nonzero (2 broadcasts, 4 reads, 16 plain multiply-adds per nonzero): %6.1f FMA/clk/CU\n",
+           per_cu_clk((double)CU * 1024 * iters * 64, ms)); }
   printf("published fp32 vector peak: 128 FMA/clk/CU (packed); 4 bytes per multiply-add from LDS at the measured\n"
          "ds_read_b128 rate would allow at most (B/clk/CU above) / 4 FMA/clk/CU\n");
   return 0;
