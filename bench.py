@@ -181,7 +181,7 @@ def widened_cases(wl, spdl, torch):
     nL = torch.randn((N.m, 128), device="cuda")
     nRn = torch.randn((128, N.k), device="cuda")
     nout = torch.empty(N.nnz, device="cuda")
-    out.append(WidenedCase("lstm90_rhs_not_transposed", "sddmm_nt", "lane_per_entry", N.nnz,
+    out.append(WidenedCase("lstm90_rhs_not_transposed", "sddmm_nt", "lane_nt", N.nnz,
                            lambda: spdl.spdl_sddmm_nt(N.m, N.k, 128, N.nnz, nro, nci, None, nL, nRn, nout),
                            sddmm_bytes(N.m, N.k, 128, N.nnz), 2.0 * N.nnz * 128, dims=(N.m, N.k, 128)))
     return out

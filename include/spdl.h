@@ -89,7 +89,9 @@ int spdl_sddmm_scaled_f16(int m, int k, int n, int nnz, const int* row_offsets, 
  * L by an n x k matrix):
  *   out_values[p] = sum_j L[i,j] * Rn[j, column_indices[p]]   (times values[p] when values != NULL).
  *   Rn : DEVICE [n*k], row-major n x k.  values : DEVICE [nnz] or NULL; not the array out_values.
- *   Everything else as spdl_sddmm; k*n < 2^31.  Any n and alignment. */
+ *   Everything else as spdl_sddmm; k*n < 2^31.  Any n and alignment; fp32 with n % 4 == 0,
+ *   n <= 128, k % 4 == 0 and 16-byte aligned L and Rn runs at about the speed of spdl_sddmm (slabs of
+ *   Rn are transposed on the chip), everything else in a plain kernel an order of magnitude slower. */
 int spdl_sddmm_nt(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                   const float* values, const float* L, const float* Rn, float* out_values, void* stream);
 int spdl_sddmm_nt_f16(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,

@@ -35,6 +35,13 @@
 // inside a slab are not a prefix of the look-ahead, its cursor is frozen, and the row is redone
 // by direct gathers after the last slab.
 // Needs n % 4 == 0, n <= 128, 16-byte aligned L and R.
+//
+// NT: the right-hand operand is given not transposed (n x k, row-major: the general SDDMM of
+// the same section's footnote).  A slab is then 128 consecutive columns of every row of Rn.  It
+// is fetched as it lies (rows of 512 contiguous bytes, direct-to-LDS, while the previous slab
+// is being worked on) into a staging area and transposed from there into the layout above by
+// LDS reads and writes, between two barriers; one slab buffer instead of two.  Needs k % 4 == 0
+// and a 16-byte aligned Rn as well.
 #pragma once
 #include "common.hpp"
 #include "sddmm_slab.hpp"
@@ -45,6 +52,12 @@ constexpr int kLaneS = 128;                          // rows of R per slab
 constexpr int kLaneRegion = kLaneS * 256 + 16;       // one 64-column half of a slab
 constexpr int kLaneBuf = 2 * kLaneRegion;
 constexpr int kLaneLdsBytes = 2 * kLaneBuf;
+// NT staging: rows 2i and 2i+1 of the slab of Rn interleaved in 16-byte pieces (piece q of row
+// 2i+r at 32 q + 16 r), 32 bytes of padding per pair: the 16-byte piece q of row c then starts in
+// bank group (c + 2 q) mod 16, so sixteen lanes reading one piece each of sixteen consecutive
+// rows do not collide.
+constexpr int kLanePairBytes = 1024 + 32;
+constexpr int kLaneNtLdsBytes = kLaneBuf + 64 * kLanePairBytes;
 
 // The two 16-byte LDS reads of one step: 32 bytes of the R row at byte offset `off`, from x on.
 __device__ __forceinline__ void lane_read(const char* lds, int off, int x, f32x4& b0, f32x4& b1) {
@@ -80,7 +93,7 @@ __device__ __forceinline__ float quad_sum(float a) {
 // RPG  = sparse rows per 16-lane group: the workgroup owns 64*RPG consecutive rows.
 // NCHD = the look-ahead per row, in chunks of 16 column indices: a row may have up to 16*NCHD
 //        nonzeros in one slab before it needs a second round in that slab (a full wait).
-template <int RPG, int NCHD, bool SCALED>
+template <int RPG, int NCHD, bool SCALED, bool NT = false>
 __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
     int m, int k, int n, int nnz, int ksplit, int slabs_per_part, int panels,
     const int* __restrict__ row_offsets, const int* __restrict__ column_indices,
@@ -144,6 +157,44 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
       const unsigned m0v = dst + (unsigned)dst_off[i];
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                    :: "s"(m0v), "v"(voff), "s"(base) : "memory", "m0");
+    }
+  };
+
+  // NT: copy i of wave w fetches rows c = 2 (16 i + w) and c + 1 of Rn (even lanes the first, odd
+  // lanes the second), columns slab start + 4 (lane / 2) .. + 3: lane L's 16 bytes land at
+  // M0 + 16 L, which is the interleaved staging layout.  Rows past n are clamped to row 0 (the
+  // matching values of L are zero), column quads past k to the slab's first quad (no valid
+  // nonzero refers to them).
+  auto fetch_slab_nt = [&](int q) {
+    const int slab_start = k0 + q * S;
+    const int quad = slab_start + 4 * (lane >> 1);
+    const unsigned colb = (unsigned)(quad < k ? quad : slab_start) * 4u;
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i) {
+      const int pair = i * 16 + wave;
+      const int c = 2 * pair + (lane & 1);
+      const unsigned voff = (unsigned)(c < n ? c : 0) * (unsigned)k * 4u + colb;
+      const unsigned m0v = lds_base + (unsigned)(kLaneBuf + pair * kLanePairBytes);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :: "s"(m0v), "v"(voff), "s"(R) : "memory", "m0");
+    }
+  };
+  // NT: staging -> slab buffer 0.  Thread (c = tid % 128, quads tid / 128 + 8 i) reads the four
+  // values Rn[c, 4 quad .. + 3] and writes them to rows 4 quad .. + 3 of the slab, column c: the
+  // 64 lanes of a wave write 64 consecutive columns of one row (all banks once).
+  auto transpose_slab_nt = [&]() {
+    const int c = tid & 127;
+    const char* src = lds_raw + kLaneBuf + (c >> 1) * kLanePairBytes + (c & 1) * 16;
+    char* dst = lds_raw + (c >> 6) * kLaneRegion + (c & 63) * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int quad = (tid >> 7) + 8 * i;
+      const f32x4 v = *reinterpret_cast<const f32x4*>(src + quad * 32);
+      float* d = reinterpret_cast<float*>(dst + quad * 1024);
+      d[0] = v.x;
+      d[64] = v.y;
+      d[128] = v.z;
+      d[192] = v.w;
     }
   };
 
@@ -231,15 +282,20 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
     }
   };
 
-  copy_stage(0);
+  if constexpr (NT) fetch_slab_nt(0);
+  else copy_stage(0);
 #pragma unroll
   for (int j = 0; j < RPG; ++j) fetch(j, p[j]);
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
+  if constexpr (NT) {
+    transpose_slab_nt();
+    __syncthreads();
+  }
 
   for (int s = 0; s < nslabs; ++s) {
     const int slab_start = k0 + s * S;
-    const int buf_off = (s & 1) * kLaneBuf;
+    const int buf_off = NT ? 0 : (s & 1) * kLaneBuf;
     // LDS byte offset of R row c in region 0 = (c << 8) + row_base
     const int row_base = buf_off - slab_start * 256;
     bool first = true, more;
@@ -255,7 +311,10 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
           if (SCALED) asm volatile("" :: "v"(sc[j][i]));
         }
       store_pending();
-      if (first && s + 1 < nslabs) copy_stage(s + 1);
+      if (first && s + 1 < nslabs) {
+        if constexpr (NT) fetch_slab_nt(s + 1);       // the staging area was emptied before this stage
+        else copy_stage(s + 1);
+      }
       first = false;
       more = false;
       // First the look-ahead of every row is counted and replaced by the next one, so that all
@@ -357,6 +416,12 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
     } while (more);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
+    if constexpr (NT) {
+      if (s + 1 < nslabs) {                           // the slab is done with, the next one has arrived
+        transpose_slab_nt();
+        __syncthreads();
+      }
+    }
   }
   store_pending();
 
@@ -368,9 +433,20 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
       const int b0 = k0 <= 0 ? rb : sd_lower_bound16(column_indices, rb, re, k0, sub, l16, last_nz);
       int e = k1 >= k ? re : sd_lower_bound16(column_indices, rb, re, k1, sub, l16, last_nz);
       e = max(e, b0);
-      for (int t = b0; t < e; t += 16)
-        sd_strip_direct_call<float>(n, t, e, l16, L + (size_t)row[j] * n, column_indices, R, out,
-                                    SCALED ? scale : nullptr);
+      if constexpr (NT) {
+        // one lane per stored entry, the plain definition
+        for (int t = b0 + l16; t < e; t += 16) {
+          const float* lrow = L + (size_t)row[j] * n;
+          const float* rcol = R + column_indices[t];
+          float acc = 0.f;
+          for (int c = 0; c < n; ++c) acc = __builtin_fmaf(lrow[c], rcol[(size_t)c * k], acc);
+          out[t] = SCALED ? acc * scale[t] : acc;
+        }
+      } else {
+        for (int t = b0; t < e; t += 16)
+          sd_strip_direct_call<float>(n, t, e, l16, L + (size_t)row[j] * n, column_indices, R, out,
+                                      SCALED ? scale : nullptr);
+      }
     }
 }
 

@@ -3,8 +3,9 @@
 // coalesced without any work): out[p] = sum_j L[i,j] * Rn[j, c_p], optionally times values[p].
 // One lane per stored entry (consecutive entries of a row have ascending columns, so for a
 // fixed j the lanes of a wave read one row of Rn left to right); each lane finds its row with
-// a binary search in the row offsets.  A plain kernel for completeness: two loads per
-// multiply-add, any n, any alignment.
+// a binary search in the row offsets.  The plain fallback (two loads per multiply-add, any n,
+// any alignment, fp32 and fp16): fp32 dot products of up to 128 columns with k % 4 == 0 go through
+// the lane kernel's NT mode instead, which transposes slabs of Rn inside LDS.
 #pragma once
 #include "common.hpp"
 

@@ -331,13 +331,14 @@ SddmmSlabShape sddmm_slab_shape(int m, int k, int n) {
 // slab of 128 columns), and the split of A's columns over workgroups that fills the machine.
 struct SddmmLaneShape { int rpg, nchd, ksplit, spp, panels; };
 
-SddmmLaneShape sddmm_lane_shape(int m, int k, int nnz) {
+SddmmLaneShape sddmm_lane_shape(int m, int k, int nnz, bool one_row_per_group = false) {
   SddmmLaneShape sh;
   const double d = (m > 0 && k > 0) ? (double)nnz / ((double)m * (double)k) : 0.0;
   const double mean = kLaneS * d, sd = std::sqrt(mean * std::max(0.0, 1.0 - d));
   sh.nchd = std::max(1, std::min(4, (int)std::ceil((mean + 4.0 * sd + 1.0) / 16.0)));
   sh.rpg = d >= 0.15 ? 1 : 2;
   if (sh.rpg == 2 && m <= kSdRows * kComputeUnits / 8) sh.rpg = 1;      // too few rows to share
+  if (one_row_per_group) sh.rpg = 1;
   sh.panels = (m + kSdRows * sh.rpg - 1) / (kSdRows * sh.rpg);
   const int total = std::max(1, (k + kLaneS - 1) / kLaneS);
   const int want = std::max(1, std::min(total, (kComputeUnits + sh.panels - 1) / sh.panels));
@@ -346,21 +347,22 @@ SddmmLaneShape sddmm_lane_shape(int m, int k, int nnz) {
   return sh;
 }
 
-template <int RPG, int NCHD>
+template <int RPG, int NCHD, bool NT = false>
 int launch_sddmm_lane(const SddmmLaneShape& sh, int grid, int m, int k, int n, int nnz, const int* ro, const int* ci,
                       const float* L, const float* R, float* out, const float* scale, hipStream_t st) {
   static std::atomic<bool> configured{false};
-  const void* plain = reinterpret_cast<const void*>(sddmm_lane_kernel<RPG, NCHD, false>);
-  const void* scaled = reinterpret_cast<const void*>(sddmm_lane_kernel<RPG, NCHD, true>);
+  constexpr int lds = NT ? kLaneNtLdsBytes : kLaneLdsBytes;
+  const void* plain = reinterpret_cast<const void*>(sddmm_lane_kernel<RPG, NCHD, false, NT>);
+  const void* scaled = reinterpret_cast<const void*>(sddmm_lane_kernel<RPG, NCHD, true, NT>);
   if (!configured.load()) {
     for (const void* f : {plain, scaled})
-      if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kLaneLdsBytes) != hipSuccess)
+      if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
         return SPDL_ERR_LAUNCH;
     configured.store(true);
   }
   int ksplit = sh.ksplit, spp = sh.spp, panels = sh.panels;
   void* args[] = {&m, &k, &n, &nnz, &ksplit, &spp, &panels, &ro, &ci, &L, &R, &out, &scale};
-  return hipLaunchKernel(scale ? scaled : plain, dim3(grid), dim3(kSdThreads), args, kLaneLdsBytes, st) == hipSuccess
+  return hipLaunchKernel(scale ? scaled : plain, dim3(grid), dim3(kSdThreads), args, lds, st) == hipSuccess
              ? SPDL_OK : SPDL_ERR_LAUNCH;
 }
 
@@ -569,6 +571,24 @@ int sddmm_nt_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, co
   if (m == 0 || nnz == 0) return SPDL_OK;
   if (!ro || !ci || !out || values == out || (n > 0 && (!L || !Rn))) return SPDL_ERR_INVALID;
   (void)hipGetLastError();
+  if constexpr (sizeof(T) == 4) {
+    // dot products of up to 128 columns: the lane kernel, which fetches its slabs of Rn as they lie
+    // and transposes them inside LDS (32-bit byte offsets into Rn: n * k * 4 < 2^31)
+    if (sddmm_lane_usable<T>(n, nnz, L, Rn) && k % 4 == 0 && m >= 64 && (int64_t)n * k < ((int64_t)1 << 29) &&
+        g_forced[1].load() < 0) {
+      // (one sparse row per group: the transposing pass needs registers that two rows' L values take)
+      const SddmmLaneShape sh = sddmm_lane_shape(m, k, nnz, true);
+      const int grid = slab_grid_size(sh.panels, sh.ksplit);
+      hipStream_t st = static_cast<hipStream_t>(stream);
+      int rc = SPDL_ERR_UNSUPPORTED;
+#define SPDL_LANE_NT(NCHD) \
+  if (sh.nchd == NCHD) rc = launch_sddmm_lane<1, NCHD, true>(sh, grid, m, k, n, nnz, ro, ci, L, Rn, out, values, st);
+      SPDL_LANE_NT(1) SPDL_LANE_NT(2) SPDL_LANE_NT(3) SPDL_LANE_NT(4)
+#undef SPDL_LANE_NT
+      if (rc != SPDL_OK) return rc;
+      return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
+    }
+  }
   sddmm_nt_kernel<T><<<dim3((nnz + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
       m, k, n, nnz, ro, ci, L, Rn, out, values);
   return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;

@@ -334,6 +334,51 @@ def test_sddmm_nt(g, oracle_lib, n):
         g.assert_close(outh.cpu().numpy(), refh, Sh, g.TOL_F16, f"sddmm nt f16 n={n}")
 
 
+@pytest.mark.parametrize("n", [4, 64, 100, 128])
+def test_sddmm_nt_slab_path(g, oracle_lib, n):
+    """k % 4 == 0, n % 4 == 0, n <= 128, 16-byte aligned operands: the slabs of Rn are fetched as
+    they lie and transposed inside LDS.  Ragged last slab (160 = 128 + 32 columns), rows that are
+    not ascending (redone entry by entry), the scaled form."""
+    import torch
+    import paper_2006_10901_amd as spdl
+    cases = [wl.adversarial_csr(203, 160, 2600 + n, sorted_cols=True),
+             wl.adversarial_csr(203, 160, 2600 + n, sorted_cols=False),
+             wl.uniform_mask_csr(700, 1000, 0.3, 2650 + n),        # 8 slabs, three look-ahead chunks
+             wl.uniform_mask_csr(64, 132, 0.9, 2660 + n)]          # nearly dense rows: several rounds per slab
+    for A in cases:
+        L, Rn = wl.dense(A.m, n, 2601 + n), wl.dense(n, A.k, 2602 + n)
+        ref, S = oracle_lib.sddmm_nt(A.m, A.k, n, A.row_offsets, A.column_indices, L, Rn)
+        d = g.DevCsr(A)
+        out = torch.full((A.nnz,), float("nan"), device="cuda")
+        spdl.spdl_sddmm_nt(A.m, A.k, n, A.nnz, d.ro, d.ci, None, g.dev(L), g.dev(Rn), out)
+        torch.cuda.synchronize()
+        g.assert_close(out.cpu().numpy(), ref, S, g.TOL_F32, f"sddmm nt {A.m}x{A.k} n={n}")
+        out.fill_(float("nan"))
+        spdl.spdl_sddmm_nt(A.m, A.k, n, A.nnz, d.ro, d.ci, d.val, g.dev(L), g.dev(Rn), out)
+        torch.cuda.synchronize()
+        v = A.values.astype(np.float64)
+        g.assert_close(out.cpu().numpy(), v * ref, np.abs(v) * S, g.TOL_F32, f"scaled sddmm nt {A.m}x{A.k} n={n}")
+
+
+def test_sddmm_nt_lstm_full_size(g, oracle_lib):
+    """The weight-gradient shape of the LSTM problem at 90 % sparsity with R given as its transpose
+    (128 x 10240): every output against the oracle, and bit for bit against the transposed entry point,
+    which forms each dot product in the same order."""
+    import torch
+    import paper_2006_10901_amd as spdl
+    w = wl.lstm(90)
+    A, L, R = w["A"], w["L"], w["R"]
+    Rn = np.ascontiguousarray(R.T)
+    ref, S = oracle_lib.sddmm_nt(A.m, A.k, 128, A.row_offsets, A.column_indices, L, Rn)
+    d = g.DevCsr(A)
+    out = torch.full((A.nnz,), float("nan"), device="cuda")
+    spdl.spdl_sddmm_nt(A.m, A.k, 128, A.nnz, d.ro, d.ci, None, g.dev(L), g.dev(Rn), out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    g.assert_close(got, ref, S, g.TOL_F32, "lstm 90 % sddmm nt")
+    assert np.array_equal(got, g.gpu_sddmm(A, L, R, 128, dA=d))
+
+
 def test_sddmm_nt_attention_size_equals_transposed_form(g, oracle_lib):
     # the attention scores of one head, computed from K^T (64 x 4096) instead of K
     import torch
