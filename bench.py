@@ -200,6 +200,15 @@ def extra_cases(groups, wl, spdl, torch):
             w = wl.transformer_ffn(which)
             extra.append(Case(f"ffn_W{which}", "spmm", w["A"], 4096, (w["B"],), spdl, torch))
             extra.append(Case(f"ffn_W{which}", "sddmm", w["A"], 4096, (w["L"], w["R"]), spdl, torch))
+            # the same SDDMM with the row order that SpMM uses (spdl_sddmm_ordered)
+            A = w["A"]
+            ro, ci = dev(A.row_offsets), dev(A.column_indices)
+            order = dev(spdl.spdl_build_row_order(A.m, A.row_offsets))
+            L, R, out = dev(w["L"]), dev(w["R"]), torch.empty(A.nnz, device="cuda")
+            extra.append(WidenedCase(f"ffn_W{which}", "sddmm_ordered", extra[-1].kernel, A.nnz,
+                                     lambda A=A, ro=ro, ci=ci, order=order, L=L, R=R, out=out:
+                                     spdl.spdl_sddmm_ordered(A.m, A.k, 4096, A.nnz, ro, ci, order, L, R, out),
+                                     sddmm_bytes(A.m, A.k, 4096, A.nnz), 2.0 * A.nnz * 4096, dims=(A.m, A.k, 4096)))
     if "attention" in groups:               # one head of the banded sparse attention
         w = wl.attention(0)
         extra.append(Case("attention_head", "sddmm", w["A"], 64, (w["Q"], w["K"]), spdl, torch))
@@ -236,6 +245,17 @@ def extra_cases(groups, wl, spdl, torch):
                                      lambda A=A, ro=ro, ci=ci, val=val, B=B, C=C:
                                      spdl.spdl_spmm(A.m, A.k, 128, A.nnz, ro, ci, val, None, B, C),
                                      spmm_bytes(A.m, A.k, 128, A.nnz), 2.0 * A.nnz * 128, dims=(A.m, A.k, 128)))
+            # SDDMM on the same topology (its interface has no row order)
+            sd = Case(tag + "_natural_order", "sddmm", A, 128, (wl.dense(A.m, 128, 515), wl.dense(A.k, 128, 516)), spdl, torch)
+            extra.append(sd)
+            # ... and with the sorted order handed to spdl_sddmm_ordered
+            order = dev(spdl.spdl_build_row_order(A.m, A.row_offsets))
+            L, R = dev(wl.dense(A.m, 128, 515)), dev(wl.dense(A.k, 128, 516))
+            out = torch.empty(A.nnz, device="cuda")
+            extra.append(WidenedCase(tag + "_sorted_order", "sddmm_ordered", sd.kernel, A.nnz,
+                                     lambda A=A, ro=ro, ci=ci, order=order, L=L, R=R, out=out:
+                                     spdl.spdl_sddmm_ordered(A.m, A.k, 128, A.nnz, ro, ci, order, L, R, out),
+                                     sddmm_bytes(A.m, A.k, 128, A.nnz), 2.0 * A.nnz * 128, dims=(A.m, A.k, 128)))
     if "widened" in groups:
         extra += widened_cases(wl, spdl, torch)
     return extra
@@ -424,6 +444,10 @@ def main():
         ffn = [c for c in extra if c.name.startswith("ffn_W") and c.op in ("spmm", "sddmm")]
         t = sum(float(np.mean(c.ms)) for c in ffn) * 1e-3
         result["transformer_ffn_gflops"] = round(sum(c.flops for c in ffn) / t / 1e9, 1)
+        # the same four products with the SDDMMs given the row order too
+        ffo = [c for c in extra if c.name.startswith("ffn_W") and c.op in ("spmm", "sddmm_ordered")]
+        to = sum(float(np.mean(c.ms)) for c in ffo) * 1e-3
+        result["transformer_ffn_gflops_sddmm_with_row_order"] = round(sum(c.flops for c in ffo) / to / 1e9, 1)
 
     if not args.no_cpu:
         import oracle

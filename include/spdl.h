@@ -71,6 +71,14 @@ int spdl_spmm(int m, int k, int n, int nnz, const int* row_offsets, const int* c
 int spdl_sddmm(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                const float* L, const float* R, float* out_values, void* stream);
 
+/* SDDMM with the row order of SpMM (paper Sec. "Row Swizzle Load Balancing"; the paper applies the
+ * swizzle to SpMM, the kernels here that give a sparse row to one lane group profit in the same way):
+ *   row_order : DEVICE int32[m], a permutation of [0,m) (spdl_build_row_order), or NULL.
+ *   It changes which workgroup computes which row, never a result; kernels that split the work by
+ *   nonzeros ignore it.  Everything else as spdl_sddmm. */
+int spdl_sddmm_ordered(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                       const int* row_order, const float* L, const float* R, float* out_values, void* stream);
+
 /* General SDDMM (same section: the strict definition, with the element-wise scaling by the sparse
  * matrix that the deep-learning form leaves out; the footnote there prices it at one load and
  * one multiply before the store):

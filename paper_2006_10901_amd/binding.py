@@ -21,7 +21,7 @@ EXPORTS = (
     "spdl_variant_name", "spdl_status_string", "spdl_version",
     "spdl_spmm_bias_relu", "spdl_spmm_bias_relu_f16", "spdl_csr_softmax", "spdl_build_transpose_host",
     "spdl_permute_values", "spdl_sddmm_scaled", "spdl_sddmm_scaled_f16",
-    "spdl_sddmm_nt", "spdl_sddmm_nt_f16", "spdl_spmm_f16_i16",
+    "spdl_sddmm_nt", "spdl_sddmm_nt_f16", "spdl_spmm_f16_i16", "spdl_sddmm_ordered",
 )
 
 
@@ -109,6 +109,17 @@ def spdl_sddmm(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stre
         _dev(column_indices, torch.int32, "column_indices"), _dev(L, torch.float32, "L"),
         _dev(R, torch.float32, "R"), _dev(out_values, torch.float32, "out_values"), _stream(stream)),
         "spdl_sddmm")
+    return out_values
+
+
+def spdl_sddmm_ordered(m, k, n, nnz, row_offsets, column_indices, row_order, L, R, out_values, stream=None):
+    import torch
+    _check(lib().spdl_sddmm_ordered(
+        int(m), int(k), int(n), int(nnz), _dev(row_offsets, torch.int32, "row_offsets"),
+        _dev(column_indices, torch.int32, "column_indices"),
+        _dev(row_order, torch.int32, "row_order", allow_none=True), _dev(L, torch.float32, "L"),
+        _dev(R, torch.float32, "R"), _dev(out_values, torch.float32, "out_values"), _stream(stream)),
+        "spdl_sddmm_ordered")
     return out_values
 
 

@@ -36,6 +36,8 @@
 // by direct gathers after the last slab.
 // Needs n % 4 == 0, n <= 128, 16-byte aligned L and R.
 //
+// Row order (optional): see the row setup below.
+//
 // NT: the right-hand operand is given not transposed (n x k, row-major: the general SDDMM of
 // the same section's footnote).  A slab is then 128 consecutive columns of every row of Rn.  It
 // is fetched as it lies (rows of 512 contiguous bytes, direct-to-LDS, while the previous slab
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
     int m, int k, int n, int nnz, int ksplit, int slabs_per_part, int panels,
     const int* __restrict__ row_offsets, const int* __restrict__ column_indices,
     const float* __restrict__ L, const float* __restrict__ R, float* __restrict__ out,
-    const float* __restrict__ scale) {
+    const float* __restrict__ scale, const int* __restrict__ row_order) {
   constexpr int S = kLaneS;
   constexpr int WIN = 16 * NCHD;                // nonzeros per round
   constexpr int kCopies = S * 2 / 4 / 16;       // 1 KB direct-to-LDS loads per wave per slab
@@ -205,8 +207,15 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
   bool safe = true;                  // no load of the look-ahead can pass the end of the arrays
 #pragma unroll
   for (int j = 0; j < RPG; ++j) {
-    const int r = (panel * kSdRows + wave * 4 + sub) * RPG + j;
-    const bool ok = r < m;
+    // Without a row order a workgroup owns 64*RPG consecutive rows.  With one (rows by decreasing
+    // length, paper Sec. "Row Swizzle Load Balancing"), the 4*RPG rows of a wave are adjacent in
+    // the order (a bundle of similar lengths, so the groups of a wave finish together) and a
+    // workgroup takes every panels-th bundle, so every workgroup gets the same mix of long and
+    // short rows.
+    const int slot = row_order ? ((wave * panels + panel) * 4 + sub) * RPG + j
+                               : (panel * kSdRows + wave * 4 + sub) * RPG + j;
+    const bool ok = slot < m;
+    const int r = ok && row_order ? row_order[slot] : slot;
     row[j] = ok ? r : -1;
     const int rb = ok ? row_offsets[r] : 0;
     const int re = ok ? row_offsets[r + 1] : 0;

@@ -14,7 +14,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_dma_kernel(
     int m, int k, int n, int nnz, int ksplit, int slabs_per_part, int panels,
     const int* __restrict__ row_offsets, const int* __restrict__ column_indices,
     const float* __restrict__ L, const float* __restrict__ R, float* __restrict__ out,
-    const float* __restrict__ scale) {
+    const float* __restrict__ scale, const int* __restrict__ row_order) {
   using T = float;
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
   constexpr int CW = 64 * U;                    // columns per stage
@@ -86,7 +86,10 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_dma_kernel(
 
   SdRow r;
   {
-    const int row = panel * kSdRows + wave * 4 + sub;
+    // With a row order (rows by decreasing length): the four rows of a wave are adjacent in the
+    // order and a workgroup takes every panels-th such bundle, as in SpMM.
+    const int slot = row_order ? (wave * panels + panel) * 4 + sub : panel * kSdRows + wave * 4 + sub;
+    const int row = slot < m && row_order ? row_order[slot] : slot;
     r.row = row < m ? row : -1;
     const int rb = row < m ? row_offsets[row] : 0;
     r.row_end = row < m ? row_offsets[row + 1] : 0;

@@ -349,7 +349,8 @@ SddmmLaneShape sddmm_lane_shape(int m, int k, int nnz, bool one_row_per_group = 
 
 template <int RPG, int NCHD, bool NT = false>
 int launch_sddmm_lane(const SddmmLaneShape& sh, int grid, int m, int k, int n, int nnz, const int* ro, const int* ci,
-                      const float* L, const float* R, float* out, const float* scale, hipStream_t st) {
+                      const float* L, const float* R, float* out, const float* scale, hipStream_t st,
+                      const int* order = nullptr) {
   static std::atomic<bool> configured{false};
   constexpr int lds = NT ? kLaneNtLdsBytes : kLaneLdsBytes;
   const void* plain = reinterpret_cast<const void*>(sddmm_lane_kernel<RPG, NCHD, false, NT>);
@@ -361,7 +362,7 @@ int launch_sddmm_lane(const SddmmLaneShape& sh, int grid, int m, int k, int n, i
     configured.store(true);
   }
   int ksplit = sh.ksplit, spp = sh.spp, panels = sh.panels;
-  void* args[] = {&m, &k, &n, &nnz, &ksplit, &spp, &panels, &ro, &ci, &L, &R, &out, &scale};
+  void* args[] = {&m, &k, &n, &nnz, &ksplit, &spp, &panels, &ro, &ci, &L, &R, &out, &scale, &order};
   return hipLaunchKernel(scale ? scaled : plain, dim3(grid), dim3(kSdThreads), args, lds, st) == hipSuccess
              ? SPDL_OK : SPDL_ERR_LAUNCH;
 }
@@ -460,7 +461,8 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
 
 template <typename T, int U, int S, bool DEFERRED>
 int launch_sddmm_slab(const SddmmSlabShape& sh, int grid, int m, int k, int n, int nnz, const int* ro,
-                      const int* ci, const T* L, const T* R, T* out, const T* scale, hipStream_t st, bool dma) {
+                      const int* ci, const T* L, const T* R, T* out, const T* scale, hipStream_t st, bool dma,
+                      const int* order) {
   static std::atomic<bool> configured{false};
   static std::atomic<bool> configured_dma{false};
   if (dma) {
@@ -472,7 +474,7 @@ int launch_sddmm_slab(const SddmmSlabShape& sh, int grid, int m, int k, int n, i
       configured_dma.store(true);
     }
     kernel<<<dim3(grid), dim3(kSdThreads), sh.lds_bytes, st>>>(m, k, n, nnz, sh.ksplit, sh.spp, sh.panels, ro, ci,
-                                                               L, R, out, scale);
+                                                               L, R, out, scale, order);
     return SPDL_OK;
   }
   auto kernel = sddmm_slab_kernel<T, U, S, DEFERRED>;
@@ -489,7 +491,7 @@ int launch_sddmm_slab(const SddmmSlabShape& sh, int grid, int m, int k, int n, i
 
 template <typename T>
 int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const T* L, const T* R,
-               T* out, void* stream, const T* scale = nullptr) {
+               T* out, void* stream, const T* scale = nullptr, const int* order = nullptr) {
   if (!sizes_ok(m, k, n, nnz)) return SPDL_ERR_INVALID;
   if (m == 0 || nnz == 0) return SPDL_OK;
   if (!ro || !ci || !out || (n > 0 && (!L || !R))) return SPDL_ERR_INVALID;
@@ -521,7 +523,7 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
       int rc = SPDL_ERR_UNSUPPORTED;
 #define SPDL_LANE(RPG, NCHD)                                                                           \
   if (sh.rpg == RPG && sh.nchd == NCHD)                                                                \
-    rc = launch_sddmm_lane<RPG, NCHD>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st);
+    rc = launch_sddmm_lane<RPG, NCHD>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, order);
       SPDL_LANE(1, 1) SPDL_LANE(1, 2) SPDL_LANE(1, 3) SPDL_LANE(1, 4)
       SPDL_LANE(2, 1) SPDL_LANE(2, 2) SPDL_LANE(2, 3) SPDL_LANE(2, 4)
 #undef SPDL_LANE
@@ -536,9 +538,9 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
       const SddmmSlabShape sh = sddmm_slab_shape(m, k, n);
       const bool dma = li.variant == kSddmmSlabDma;
       int rc;
-      if (sh.deferred) rc = launch_sddmm_slab<T, 2, 128, true>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma);
-      else if (sh.U == 1) rc = launch_sddmm_slab<T, 1, 256, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma);
-      else rc = launch_sddmm_slab<T, 2, 128, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma);
+      if (sh.deferred) rc = launch_sddmm_slab<T, 2, 128, true>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma, order);
+      else if (sh.U == 1) rc = launch_sddmm_slab<T, 1, 256, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma, order);
+      else rc = launch_sddmm_slab<T, 2, 128, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma, order);
       if (rc != SPDL_OK) return rc;
       return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
     } else {
@@ -684,6 +686,11 @@ int spdl_permute_values(int nnz, int elem_bytes, const int* perm, const void* va
 int spdl_sddmm(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                const float* L, const float* R, float* out_values, void* stream) {
   return sddmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stream);
+}
+
+int spdl_sddmm_ordered(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                       const int* row_order, const float* L, const float* R, float* out_values, void* stream) {
+  return sddmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stream, nullptr, row_order);
 }
 
 int spdl_sddmm_nt(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,

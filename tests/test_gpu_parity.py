@@ -56,6 +56,29 @@ def test_row_order_built_by_the_library_feeds_the_kernels(g, oracle_lib):
     assert np.array_equal(c_mine, c_ident)
 
 
+def test_sddmm_with_a_row_order_gives_the_same_bits(g, oracle_lib):
+    """spdl_sddmm_ordered: the row order only moves rows between workgroups.  Skewed rows on a shape
+    that takes the lane kernel and one that takes the slab kernel for wide dot products (the two
+    that use the order; m is not a multiple of the panel), the library's sorted order and a random
+    permutation, against the oracle and bit for bit against spdl_sddmm; and a shape whose kernel
+    ignores the order."""
+    import torch
+    import paper_2006_10901_amd as spdl
+    for (m, k, n, dens, seed) in ((2100, 900, 128, 0.12, 81), (1100, 640, 260, 0.08, 83), (300, 200, 48, 0.1, 82)):
+        A = wl.lognormal_rows_csr(m, k, dens, seed)
+        L, R = wl.dense(m, n, seed + 100), wl.dense(k, n, seed + 200)
+        ref, plain = sddmm_case(g, oracle_lib, A, L, R, n, g.TOL_F32, "sddmm without an order")
+        d = g.DevCsr(A)
+        dL, dR = g.dev(L), g.dev(R)
+        orders = (spdl.spdl_build_row_order(A.m, A.row_offsets),
+                  np.random.default_rng(seed).permutation(m).astype(np.int32), None)
+        for order in orders:
+            out = torch.full((A.nnz,), float("nan"), device="cuda")
+            spdl.spdl_sddmm_ordered(m, k, n, A.nnz, d.ro, d.ci, None if order is None else g.dev(order), dL, dR, out)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy(), plain)
+
+
 def test_identity_and_permutation_return_rows_of_B_exactly(g, oracle_lib):
     m, n = 300, 128
     B = wl.dense(m, n, 3)
