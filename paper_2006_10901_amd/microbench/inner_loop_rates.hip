@@ -101,6 +101,29 @@ __global__ __launch_bounds__(1024) void lds_fed(float* out, int iters) {
     f32x4 c = *reinterpret_cast<const f32x4*>(lds + addr + 256);                                   \
     FMA_DPP(a0, av, b.x, T) FMA_DPP(a1, av, b.y, T) FMA_DPP(a2, av, b.z, T) FMA_DPP(a3, av, b.w, T) \
     FMA_DPP(a4, av, c.x, T) FMA_DPP(a5, av, c.y, T) FMA_DPP(a6, av, c.z, T) FMA_DPP(a7, av, c.w, T) }
+// The same step with the value of A moved to every lane first (one v_mov_b32_dpp) and plain
+// multiply-adds after it.
+#define SP4M(T)                                                                                    \
+  { const int addr = __builtin_amdgcn_update_dpp(0, off, 0x150 + (T), 0xf, 0xf, false) + lane_b;   \
+    const float at = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, av), 0x150 + (T), 0xf, 0xf, false)); \
+    f32x4 b = *reinterpret_cast<const f32x4*>(lds + addr);                                         \
+    a0 = __builtin_fmaf(at, b.x, a0); a1 = __builtin_fmaf(at, b.y, a1);                            \
+    a2 = __builtin_fmaf(at, b.z, a2); a3 = __builtin_fmaf(at, b.w, a3); }
+__global__ __launch_bounds__(1024) void spmm_step_mov(float* out, int iters, const int* __restrict__ rows, int nrows) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  for (int i = threadIdx.x; i < nrows * 64; i += 1024) reinterpret_cast<float*>(lds)[i] = (float)(i & 7);
+  __syncthreads();
+  const int lane_b = (threadIdx.x & 15) * 16;
+  float a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+  const int* myrows = rows + threadIdx.x;
+  for (int it = 0; it < iters; ++it) {
+    const int off = myrows[(it & 15) * 1024] % nrows * 256;
+    const float av = 0.5f + off;
+    SP4M(0) SP4M(1) SP4M(2) SP4M(3) SP4M(4) SP4M(5) SP4M(6) SP4M(7) SP4M(8) SP4M(9) SP4M(10) SP4M(11) SP4M(12) SP4M(13) SP4M(14) SP4M(15)
+  }
+  out[blockIdx.x * 1024 + threadIdx.x] = a0 + a1 + a2 + a3;
+}
+
 template <int COLS>
 __global__ __launch_bounds__(1024) void spmm_step(float* out, int iters, const int* __restrict__ rows, int nrows) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -239,6 +262,10 @@ int main() {
   CK(hipFuncSetAttribute((const void*)sddmm_lane_step, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
   { float ms = best_ms([&] { spmm_step<4><<<CU, 1024, 448 * 256>>>(out, iters, rows, 448); });
     printf("SpMM step, 4 columns per lane (1 address, 1 read, 4 DPP multiply-adds per nonzero): %6.1f FMA/clk/CU\n",
+           per_cu_clk((double)CU * 1024 * iters * 64, ms)); }
+  CK(hipFuncSetAttribute((const void*)spmm_step_mov, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+  { float ms = best_ms([&] { spmm_step_mov<<<CU, 1024, 448 * 256>>>(out, iters, rows, 448); });
+    printf("SpMM step, 4 columns per lane, value moved first (1 address, 1 DPP move, 1 read, 4 plain multiply-adds): %6.1f FMA/clk/CU\n",
            per_cu_clk((double)CU * 1024 * iters * 64, ms)); }
   { float ms = best_ms([&] { spmm_step<8><<<CU, 1024, 224 * 512>>>(out, iters, rows, 224); });
     printf("SpMM step, 8 columns per lane (1 address, 2 reads, 8 DPP multiply-adds per nonzero): %6.1f FMA/clk/CU\n",
