@@ -77,6 +77,22 @@ def test_sddmm_with_a_row_order_gives_the_same_bits(g, oracle_lib):
             spdl.spdl_sddmm_ordered(m, k, n, A.nnz, d.ro, d.ci, None if order is None else g.dev(order), dL, dR, out)
             torch.cuda.synchronize()
             assert np.array_equal(out.cpu().numpy(), plain)
+    # a single ragged panel (m < 64 rows per workgroup slot count), lane kernel forced
+    A = wl.lognormal_rows_csr(70, 260, 0.2, 84)
+    L, R = wl.dense(70, 128, 184), wl.dense(260, 128, 284)
+    ref, S = oracle_lib.sddmm(A.m, A.k, 128, A.row_offsets, A.column_indices, L, R)
+    d = g.DevCsr(A)
+    spdl.spdl_force_variant(1, 5)
+    try:
+        assert spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(70, 260, 128, A.nnz, 4, 0, 0)["variant"]) == "lane"
+        for order in (spdl.spdl_build_row_order(A.m, A.row_offsets), None):
+            out = torch.full((A.nnz,), float("nan"), device="cuda")
+            spdl.spdl_sddmm_ordered(70, 260, 128, A.nnz, d.ro, d.ci, None if order is None else g.dev(order),
+                                    g.dev(L), g.dev(R), out)
+            torch.cuda.synchronize()
+            g.assert_close(out.cpu().numpy(), ref, S, g.TOL_F32, "forced lane kernel, one ragged panel")
+    finally:
+        spdl.spdl_force_variant(1, -1)
 
 
 def test_identity_and_permutation_return_rows_of_B_exactly(g, oracle_lib):
