@@ -202,40 +202,75 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
 
   // rows of this group, their ranges of nonzeros inside [k0, k1), their quarters of L in the
   // order of use: lr[j][8 s + e] = L[row, 32 h + 8((t-s) mod 4) + e]
+  // the first slab is requested before anything else: it depends on nothing that follows
+  if constexpr (NT) fetch_slab_nt(0);
+  else copy_stage(0);
+
   int row[RPG], p_end[RPG], p[RPG];
   float lr[RPG][32];
   bool safe = true;                  // no load of the look-ahead can pass the end of the arrays
+  {
+    // Everything the set-up reads is requested before anything is waited for: the row offsets of all
+    // rows, then the quarters of L (raw), then the searches for the rows' ranges inside [k0, k1), all
+    // 2*RPG of them side by side (a round of probes costs one memory latency, not 2*RPG).
+    int rb[RPG], re[RPG];
+    bool ok[RPG];
 #pragma unroll
-  for (int j = 0; j < RPG; ++j) {
-    // Without a row order a workgroup owns 64*RPG consecutive rows.  With one (rows by decreasing
-    // length, paper Sec. "Row Swizzle Load Balancing"), the 4*RPG rows of a wave are adjacent in
-    // the order (a bundle of similar lengths, so the groups of a wave finish together) and a
-    // workgroup takes every panels-th bundle, so every workgroup gets the same mix of long and
-    // short rows.
-    const int slot = row_order ? ((wave * panels + panel) * 4 + sub) * RPG + j
-                               : (panel * kSdRows + wave * 4 + sub) * RPG + j;
-    const bool ok = slot < m;
-    const int r = ok && row_order ? row_order[slot] : slot;
-    row[j] = ok ? r : -1;
-    const int rb = ok ? row_offsets[r] : 0;
-    const int re = ok ? row_offsets[r + 1] : 0;
-    p[j] = k0 <= 0 ? rb : sd_lower_bound16(column_indices, rb, re, k0, sub, l16, last_nz);
-    p_end[j] = k1 >= k ? re : sd_lower_bound16(column_indices, rb, re, k1, sub, l16, last_nz);
-    p_end[j] = max(p_end[j], p[j]);
-    safe = safe && __builtin_amdgcn_ballot_w64(p_end[j] + WIN > nnz) == 0;
-    const float* lrow = L + (size_t)(ok ? r : 0) * n;
+    for (int j = 0; j < RPG; ++j) {
+      // Without a row order a workgroup owns 64*RPG consecutive rows.  With one (rows by decreasing
+      // length, paper Sec. "Row Swizzle Load Balancing"), the 4*RPG rows of a wave are adjacent in
+      // the order (a bundle of similar lengths, so the groups of a wave finish together) and a
+      // workgroup takes every panels-th bundle, so every workgroup gets the same mix of long and
+      // short rows.
+      const int slot = row_order ? ((wave * panels + panel) * 4 + sub) * RPG + j
+                                 : (panel * kSdRows + wave * 4 + sub) * RPG + j;
+      ok[j] = slot < m;
+      const int r = ok[j] && row_order ? row_order[slot] : slot;
+      row[j] = ok[j] ? r : -1;
+      rb[j] = ok[j] ? row_offsets[r] : 0;
+      re[j] = ok[j] ? row_offsets[r + 1] : 0;
+    }
+    f32x4 raw[RPG][8];
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
+    for (int j = 0; j < RPG; ++j) {
+      const float* lrow = L + (size_t)max(row[j], 0) * n;
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int c = 32 * h4 + 8 * ((t4 - s) & 3) + 4 * u;
-        const bool in = ok && c < n;
-        const f32x4 vv = *reinterpret_cast<const f32x4*>(lrow + (in ? c : 0));
-        lr[j][8 * s + 4 * u + 0] = in ? vv.x : 0.f;
-        lr[j][8 * s + 4 * u + 1] = in ? vv.y : 0.f;
-        lr[j][8 * s + 4 * u + 2] = in ? vv.z : 0.f;
-        lr[j][8 * s + 4 * u + 3] = in ? vv.w : 0.f;
-      }
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int c = 32 * h4 + 8 * ((t4 - s) & 3) + 4 * u;
+          raw[j][2 * s + u] = *reinterpret_cast<const f32x4*>(lrow + (c < n ? c : 0));
+        }
+    }
+    int lo[2 * RPG], hi[2 * RPG], key[2 * RPG];
+#pragma unroll
+    for (int j = 0; j < RPG; ++j) {
+      lo[2 * j] = rb[j];
+      hi[2 * j] = k0 <= 0 ? rb[j] : re[j];            // nothing to search for the first range
+      key[2 * j] = k0;
+      lo[2 * j + 1] = k1 >= k ? re[j] : rb[j];        // ... nor for the last
+      hi[2 * j + 1] = re[j];
+      key[2 * j + 1] = k1;
+    }
+    sd_lower_bound16_batch<2 * RPG>(column_indices, lo, hi, key, sub, l16, last_nz);
+#pragma unroll
+    for (int j = 0; j < RPG; ++j) {
+      p[j] = lo[2 * j];
+      p_end[j] = max(lo[2 * j + 1], p[j]);
+      safe = safe && __builtin_amdgcn_ballot_w64(p_end[j] + WIN > nnz) == 0;
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int c = 32 * h4 + 8 * ((t4 - s) & 3) + 4 * u;
+          const bool in = ok[j] && c < n;
+          const f32x4 vv = raw[j][2 * s + u];
+          lr[j][8 * s + 4 * u + 0] = in ? vv.x : 0.f;
+          lr[j][8 * s + 4 * u + 1] = in ? vv.y : 0.f;
+          lr[j][8 * s + 4 * u + 2] = in ? vv.z : 0.f;
+          lr[j][8 * s + 4 * u + 3] = in ? vv.w : 0.f;
+        }
+    }
   }
   // byte offset of step s from the start of an R row in region 0: this lane's region, its half of
   // the 256-byte row, and the rotated 32-byte piece
@@ -291,8 +326,6 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
     }
   };
 
-  if constexpr (NT) fetch_slab_nt(0);
-  else copy_stage(0);
 #pragma unroll
   for (int j = 0; j < RPG; ++j) fetch(j, p[j]);
   __builtin_amdgcn_s_waitcnt(0);

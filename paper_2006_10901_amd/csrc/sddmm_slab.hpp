@@ -55,6 +55,41 @@ __device__ __forceinline__ int sd_lower_bound16(const int* __restrict__ ci, int 
   return lo;
 }
 
+// NB such searches at once (lo[b], hi[b], key[b]; the result is left in lo[b]): the probes of all
+// of them are loaded before any is looked at, so a round costs one memory latency however many
+// searches there are.  A search with lo == hi is already finished.
+template <int NB>
+__device__ __forceinline__ void sd_lower_bound16_batch(const int* __restrict__ ci, int (&lo)[NB], int (&hi)[NB],
+                                                       const int (&key)[NB], int sub, int l16, int last_nz) {
+  while (true) {
+    bool open = false;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) open = open || hi[b] > lo[b];
+    if (!__any(open)) break;
+    int v[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const int step = (hi[b] - lo[b] + 15) >> 4;
+      const int probe = lo[b] + (l16 + 1) * step - 1;
+      v[b] = ci[min(max(probe, 0), last_nz)];
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const int len = hi[b] - lo[b];
+      const int step = (len + 15) >> 4;
+      const int probe = lo[b] + (l16 + 1) * step - 1;
+      const bool less = len > 0 && probe < hi[b] && v[b] < key[b];
+      const unsigned long long mask = __ballot(less);
+      const unsigned piece = (unsigned)(mask >> (sub * 16)) & 0xffffu;
+      const int cnt = __builtin_ctz(~piece | 0x10000u);
+      const int nlo = lo[b] + cnt * step;
+      const int nhi = min(hi[b], nlo + step - 1);
+      lo[b] = len > 0 ? nlo : lo[b];
+      hi[b] = len > 0 ? max(nhi, nlo) : hi[b];
+    }
+  }
+}
+
 // Out-of-line copy of the direct strip for the rare paths of the slab kernel, so that its
 // registers do not count against the main loop.
 template <typename T>
