@@ -34,9 +34,17 @@
 // Rows must be ascending for the slab walk; a row that is not is noticed when its nonzeros
 // inside a slab are not a prefix of the look-ahead, its cursor is frozen, and the row is redone
 // by direct gathers after the last slab.
-// Needs n % 4 == 0, n <= 128, 16-byte aligned L and R.
+// Needs n % 4 == 0, n <= 128 per launch, 16-byte aligned L and R.
 //
 // Row order (optional): see the row setup below.
+//
+// Longer dot products: the host runs the kernel once per chunk of 128 columns (L and R advanced by
+// the chunk's first column c0, row stride ld = the full length, n = the chunk's width).  ACCUM
+// passes (c0 > 0) add their sums to what out holds from the passes before: the old value of an
+// entry is fetched together with the look-ahead of the column indices, one stage before the
+// entry is stored.  Every pass walks A again, so this pays for rows that are too dense for the slab
+// kernel that keeps partial sums in registers across the chunks (sddmm_slab_dma, at most 32 entries
+// per row and slab).
 //
 // NT: the right-hand operand is given not transposed (n x k, row-major: the general SDDMM of
 // the same section's footnote).  A slab is then 128 consecutive columns of every row of Rn.  It
@@ -95,12 +103,13 @@ __device__ __forceinline__ float quad_sum(float a) {
 // RPG  = sparse rows per 16-lane group: the workgroup owns 64*RPG consecutive rows.
 // NCHD = the look-ahead per row, in chunks of 16 column indices: a row may have up to 16*NCHD
 //        nonzeros in one slab before it needs a second round in that slab (a full wait).
-template <int RPG, int NCHD, bool SCALED, bool NT = false>
+template <int RPG, int NCHD, bool SCALED, bool NT = false, bool ACCUM = false>
 __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
     int m, int k, int n, int nnz, int ksplit, int slabs_per_part, int panels,
     const int* __restrict__ row_offsets, const int* __restrict__ column_indices,
     const float* __restrict__ L, const float* __restrict__ R, float* __restrict__ out,
-    const float* __restrict__ scale, const int* __restrict__ row_order) {
+    const float* __restrict__ scale, const int* __restrict__ row_order, int ld, int c0) {
+  static_assert(!(NT && ACCUM), "the not-transposed form takes dot products of up to 128 columns");
   constexpr int S = kLaneS;
   constexpr int WIN = 16 * NCHD;                // nonzeros per round
   constexpr int kCopies = S * 2 / 4 / 16;       // 1 KB direct-to-LDS loads per wave per slab
@@ -141,8 +150,8 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
     const int lrow = rblock * 4 + sub;
     const int col = reg * 64 + l16 * 4;
     const unsigned colb = col < n ? (unsigned)col * 4u : 0u;
-    src_off[i] = (unsigned)lrow * (unsigned)n * 4u + colb;
-    src_off_last[i] = (unsigned)min(lrow, last_rows - 1) * (unsigned)n * 4u + colb;
+    src_off[i] = (unsigned)lrow * (unsigned)ld * 4u + colb;
+    src_off_last[i] = (unsigned)min(lrow, last_rows - 1) * (unsigned)ld * 4u + colb;
     dst_off[i] = reg * kLaneRegion + rblock * 1024;
   }
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds_raw;
@@ -150,7 +159,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
   // counters and then turns every later wait into a wait for everything; their completion is
   // covered by the explicit full wait that ends every stage.
   auto copy_stage = [&](int q) {
-    const char* base = reinterpret_cast<const char*>(R + (size_t)(k0 + q * S) * n);
+    const char* base = reinterpret_cast<const char*>(R + (size_t)(k0 + q * S) * ld);
     const unsigned dst = lds_base + (unsigned)((q & 1) * kLaneBuf);
     const bool last = q == nslabs - 1;
 #pragma unroll
@@ -233,7 +242,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
     f32x4 raw[RPG][8];
 #pragma unroll
     for (int j = 0; j < RPG; ++j) {
-      const float* lrow = L + (size_t)max(row[j], 0) * n;
+      const float* lrow = L + (size_t)max(row[j], 0) * ld;
 #pragma unroll
       for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -284,15 +293,18 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
   // bases (nnz < 2^29 is checked on the host).
   int cn[RPG][NCHD];
   float sc[RPG][SCALED ? NCHD : 1];
+  float pv[RPG][ACCUM ? NCHD : 1];      // what out holds at those positions from the passes before
   auto fetch = [&](int j, int from) {
     const char* cbase = reinterpret_cast<const char*>(column_indices);
     const char* vbase = reinterpret_cast<const char*>(scale);
+    const char* obase = reinterpret_cast<const char*>(out);
     if (safe) {
       const unsigned o = (unsigned)(from + perm) << 2;
 #pragma unroll
       for (int i = 0; i < NCHD; ++i) {
         cn[j][i] = *reinterpret_cast<const int*>(cbase + (o + 64u * i));
         if (SCALED) sc[j][i] = *reinterpret_cast<const float*>(vbase + (o + 64u * i));
+        if (ACCUM) pv[j][i] = *reinterpret_cast<const float*>(obase + (o + 64u * i));
       }
     } else {
 #pragma unroll
@@ -300,6 +312,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
         const unsigned o = (unsigned)min(from + perm + 16 * i, last_nz) << 2;
         cn[j][i] = *reinterpret_cast<const int*>(cbase + o);
         if (SCALED) sc[j][i] = *reinterpret_cast<const float*>(vbase + o);
+        if (ACCUM) pv[j][i] = *reinterpret_cast<const float*>(obase + o);
       }
     }
   };
@@ -351,6 +364,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
         for (int i = 0; i < NCHD; ++i) {
           asm volatile("" :: "v"(cn[j][i]));
           if (SCALED) asm volatile("" :: "v"(sc[j][i]));
+          if (ACCUM) asm volatile("" :: "v"(pv[j][i]));
         }
       store_pending();
       if (first && s + 1 < nslabs) {
@@ -363,6 +377,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
       // loads of a stage are issued before its arithmetic starts; then the strips are worked on.
       int col[RPG][NCHD], vl[RPG];
       float scv[RPG][SCALED ? NCHD : 1];
+      float pvv[RPG][ACCUM ? NCHD : 1];
       unsigned long long okm[RPG][NCHD];
 #pragma unroll
       for (int j = 0; j < RPG; ++j) {
@@ -400,6 +415,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
         for (int i = 0; i < NCHD; ++i) {
           col[j][i] = __builtin_amdgcn_inverse_ballot_w64(okm[j][i]) ? (cn[j][i] << 8) + row_base : buf_off;
           if (SCALED) scv[j][i] = sc[j][i];
+          if (ACCUM) pvv[j][i] = pv[j][i];
         }
         fetch(j, p[j]);
       }
@@ -450,7 +466,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
             keep = h4 == q ? total : keep;
             off = off_next;
           }
-          outv[j][i] = SCALED ? keep * scv[j][i] : keep;
+          outv[j][i] = (SCALED ? keep * scv[j][i] : keep) + (ACCUM ? pvv[j][i] : 0.f);
           st_mask[j][i] = okm[j][i];
         }
       }
@@ -482,6 +498,17 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
           const float* rcol = R + column_indices[t];
           float acc = 0.f;
           for (int c = 0; c < n; ++c) acc = __builtin_fmaf(lrow[c], rcol[(size_t)c * k], acc);
+          out[t] = SCALED ? acc * scale[t] : acc;
+        }
+      } else if (ld != n) {
+        // one chunk of a longer dot product: one lane per stored entry recomputes the whole sum over
+        // the columns up to this chunk's end, so that it does not matter what out holds so far
+        const float* lfull = L - c0 + (size_t)row[j] * ld;
+        const float* rfull = R - c0;
+        for (int t = b0 + l16; t < e; t += 16) {
+          const float* rrow = rfull + (size_t)column_indices[t] * ld;
+          float acc = 0.f;
+          for (int c = 0; c < c0 + n; ++c) acc = __builtin_fmaf(lfull[c], rrow[c], acc);
           out[t] = SCALED ? acc * scale[t] : acc;
         }
       } else {

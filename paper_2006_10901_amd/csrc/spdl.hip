@@ -350,29 +350,32 @@ SddmmLaneShape sddmm_lane_shape(int m, int k, int nnz, bool one_row_per_group = 
   return sh;
 }
 
-template <int RPG, int NCHD, bool NT = false>
+template <int RPG, int NCHD, bool NT = false, bool ACCUM = false>
 int launch_sddmm_lane(const SddmmLaneShape& sh, int grid, int m, int k, int n, int nnz, const int* ro, const int* ci,
                       const float* L, const float* R, float* out, const float* scale, hipStream_t st,
-                      const int* order = nullptr) {
+                      const int* order = nullptr, int ld = 0, int c0 = 0) {
   static std::atomic<bool> configured{false};
   constexpr int lds = NT ? kLaneNtLdsBytes : kLaneLdsBytes;
-  const void* plain = reinterpret_cast<const void*>(sddmm_lane_kernel<RPG, NCHD, false, NT>);
-  const void* scaled = reinterpret_cast<const void*>(sddmm_lane_kernel<RPG, NCHD, true, NT>);
+  const void* plain = reinterpret_cast<const void*>(sddmm_lane_kernel<RPG, NCHD, false, NT, ACCUM>);
+  const void* scaled = reinterpret_cast<const void*>(sddmm_lane_kernel<RPG, NCHD, true, NT, ACCUM>);
   if (!configured.load()) {
     for (const void* f : {plain, scaled})
       if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
         return SPDL_ERR_LAUNCH;
     configured.store(true);
   }
+  if (ld == 0) ld = n;
   int ksplit = sh.ksplit, spp = sh.spp, panels = sh.panels;
-  void* args[] = {&m, &k, &n, &nnz, &ksplit, &spp, &panels, &ro, &ci, &L, &R, &out, &scale, &order};
+  void* args[] = {&m, &k, &n, &nnz, &ksplit, &spp, &panels, &ro, &ci, &L, &R, &out, &scale, &order, &ld, &c0};
   return hipLaunchKernel(scale ? scaled : plain, dim3(grid), dim3(kSdThreads), args, lds, st) == hipSuccess
              ? SPDL_OK : SPDL_ERR_LAUNCH;
 }
 
 template <typename T>
 bool sddmm_lane_usable(int n, int nnz, const void* L, const void* R) {
-  return sizeof(T) == 4 && sddmm_group_usable<T>(n, L, R) && n <= 128 && nnz < (1 << 29);
+  // (dot products longer than 128 columns take one pass per 128 columns; 32-bit byte offsets inside
+  // a slab of R: 128 rows * n * 4 < 2^31)
+  return sizeof(T) == 4 && sddmm_group_usable<T>(n, L, R) && n < (1 << 21) && nnz < (1 << 29);
 }
 
 template <typename T>
@@ -405,7 +408,10 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
     const bool fits = n <= 128 || 128.0 * (double)nnz / ((double)m * (double)k) <= 16.0;
     // dot products of 65..128 columns: the lane kernel, as long as a panel of 64 rows meets the
     // same row of R at least once on average
-    const bool lane = sddmm_lane_usable<T>(n, nnz, L, R) && n > 64 && m >= 512 && reuse >= 1.0;
+    // ... and longer dot products of rows too dense for the slab kernel's 32 partial sums per row and
+    // slab, in passes of 128 columns
+    const bool lane = sddmm_lane_usable<T>(n, nnz, L, R) && m >= 512 && reuse >= 1.0 &&
+                      ((n > 64 && n <= 128) || (n > 128 && !fits));
     variant = !fast_ok ? kSddmmRowstrip
               : lane   ? kSddmmLane
               : (sizeof(T) == 4 && reuse >= 2.0 && worth && m >= 512 && fits && nnz < (1 << 29)) ? kSddmmSlabDma
@@ -421,7 +427,7 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
   info->block_threads = 256;
   info->grid_y = 1;
   if (variant == kSddmmLane) {
-    const SddmmLaneShape sh = sddmm_lane_shape(m, k, nnz);
+    const SddmmLaneShape sh = sddmm_lane_shape(m, k, nnz, n > 128);
     info->vec = 8;
     info->lanes_per_row = 2;
     info->rows_per_block = kSdRows * sh.rpg;
@@ -522,16 +528,25 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
   }
   if (li.variant == kSddmmLane) {
     if constexpr (sizeof(T) == 4) {
-      const SddmmLaneShape sh = sddmm_lane_shape(m, k, nnz, false, scale != nullptr);
-      int rc = SPDL_ERR_UNSUPPORTED;
+      const SddmmLaneShape sh = sddmm_lane_shape(m, k, nnz, n > 128, scale != nullptr);
+      const int grid = slab_grid_size(sh.panels, sh.ksplit);
+      // one pass per chunk of 128 columns; passes after the first add to what out holds
+      for (int c0 = 0; c0 < n; c0 += 128) {
+        const int nc = std::min(128, n - c0);
+        int rc = SPDL_ERR_UNSUPPORTED;
 #define SPDL_LANE(RPG, NCHD)                                                                           \
-  if (sh.rpg == RPG && sh.nchd == NCHD)                                                                \
-    rc = launch_sddmm_lane<RPG, NCHD>(sh, slab_grid_size(sh.panels, sh.ksplit), m, k, n, nnz, ro, ci, L, R, out, \
-                                      scale, st, order);
-      SPDL_LANE(1, 1) SPDL_LANE(1, 2) SPDL_LANE(1, 3) SPDL_LANE(1, 4)
-      SPDL_LANE(2, 1) SPDL_LANE(2, 2)
+  if (sh.rpg == RPG && sh.nchd == NCHD) {                                                              \
+    if (c0 == 0)                                                                                       \
+      rc = launch_sddmm_lane<RPG, NCHD>(sh, grid, m, k, nc, nnz, ro, ci, L, R, out, scale, st, order, n, 0); \
+    else if constexpr (RPG == 1)                                                                       \
+      rc = launch_sddmm_lane<1, NCHD, false, true>(sh, grid, m, k, nc, nnz, ro, ci, L + c0, R + c0, out, scale, st, \
+                                                   order, n, c0);                                      \
+  }
+        SPDL_LANE(1, 1) SPDL_LANE(1, 2) SPDL_LANE(1, 3) SPDL_LANE(1, 4)
+        SPDL_LANE(2, 1) SPDL_LANE(2, 2)
 #undef SPDL_LANE
-      if (rc != SPDL_OK) return rc;
+        if (rc != SPDL_OK) return rc;
+      }
       return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
     } else {
       return SPDL_ERR_UNSUPPORTED;
@@ -580,7 +595,7 @@ int sddmm_nt_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, co
   if constexpr (sizeof(T) == 4) {
     // dot products of up to 128 columns: the lane kernel, which fetches its slabs of Rn as they lie
     // and transposes them inside LDS (32-bit byte offsets into Rn: n * k * 4 < 2^31)
-    if (sddmm_lane_usable<T>(n, nnz, L, Rn) && k % 4 == 0 && m >= 64 && (int64_t)n * k < ((int64_t)1 << 29) &&
+    if (sddmm_lane_usable<T>(n, nnz, L, Rn) && n <= 128 && k % 4 == 0 && m >= 64 && (int64_t)n * k < ((int64_t)1 << 29) &&
         g_forced[1].load() < 0) {
       // (one sparse row per group: the transposing pass needs registers that two rows' L values take)
       const SddmmLaneShape sh = sddmm_lane_shape(m, k, nnz, true);

@@ -353,11 +353,38 @@ def test_forced_sddmm_variants_ragged(g, oracle_lib, force, n):
                 continue                                  # fp16 only, see the mixed-precision tests
             force(1, v)
             chosen = spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"])
-            # the lane kernel holds whole dot products of up to 128 columns; wider ones go to "group"
-            expected = "group" if spdl.spdl_variant_name(1, v) == "lane" and n > 128 else spdl.spdl_variant_name(1, v)
-            assert chosen == expected
+            # (the lane kernel takes dot products of more than 128 columns in passes of 128)
+            assert chosen == spdl.spdl_variant_name(1, v)
             got = g.gpu_sddmm(A, L, R, n)
             g.assert_close(got, out, S, g.TOL_F32, f"sddmm variant {spdl.spdl_variant_name(1, v)} n={n}")
+
+
+@pytest.mark.parametrize("n", [132, 256, 388])
+def test_sddmm_long_dot_products_of_dense_rows(g, oracle_lib, n):
+    """Rows too dense for the slab kernel's 32 partial sums per row and slab, dot products longer
+    than 128 columns: the lane kernel runs once per 128 columns and adds up in the output array.
+    Default selection on a uniform mask, ragged last chunk, rows that are not ascending (recomputed
+    as a whole, whatever the earlier passes left), and the scaled form."""
+    import torch
+    import paper_2006_10901_amd as spdl
+    cases = [wl.uniform_mask_csr(1500, 1000, 0.3, 970 + n), wl.adversarial_csr(600, 300, 971 + n, sorted_cols=False)]
+    for idx, A in enumerate(cases):
+        L, R = wl.dense(A.m, n, 972 + n), wl.dense(A.k, n, 973 + n)
+        ref, S = oracle_lib.sddmm(A.m, A.k, n, A.row_offsets, A.column_indices, L, R)
+        try:
+            if idx == 1:
+                spdl.spdl_force_variant(1, 5)
+            chosen = spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"])
+            assert chosen == "lane"
+            g.assert_close(g.gpu_sddmm(A, L, R, n), ref, S, g.TOL_F32, f"lane sddmm in passes, n={n}")
+            d = g.DevCsr(A)
+            out = torch.full((A.nnz,), float("nan"), device="cuda")
+            spdl.spdl_sddmm_scaled(A.m, A.k, n, A.nnz, d.ro, d.ci, d.val, g.dev(L), g.dev(R), out)
+            torch.cuda.synchronize()
+            v = A.values.astype(np.float64)
+            g.assert_close(out.cpu().numpy(), v * ref, np.abs(v) * S, g.TOL_F32, f"scaled, in passes, n={n}")
+        finally:
+            spdl.spdl_force_variant(1, -1)
 
 
 def test_forced_sddmm_variants_fp16_and_long_rows(g, oracle_lib, force):
