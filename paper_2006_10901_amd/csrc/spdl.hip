@@ -404,14 +404,16 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
     // short dot products gain little from the slabs (a row of R is one or two cache lines) unless the
     // reuse is high, and the nonzero-split kernel does not care how the entries are laid out (a
     // banded attention mask leaves most of a panel's column ranges nearly empty)
-    const bool worth = n >= 128 || reuse >= 12.0;
+    const bool worth = n >= 128 || reuse >= 8.0;
     const bool fits = n <= 128 || 128.0 * (double)nnz / ((double)m * (double)k) <= 16.0;
     // dot products of 65..128 columns: the lane kernel, as long as a panel of 64 rows meets the
     // same row of R at least once on average
     // ... and longer dot products of rows too dense for the slab kernel's 32 partial sums per row and
     // slab, in passes of 128 columns
+    // (also where the passes are few, n <= 256, or A is sparse, under 5 %: measured faster than
+    // the slab kernel there, whose stages then hold too little work for their copies)
     const bool lane = sddmm_lane_usable<T>(n, nnz, L, R) && m >= 512 && reuse >= 1.0 &&
-                      ((n > 64 && n <= 128) || (n > 128 && !fits));
+                      ((n > 64 && n <= 128) || (n > 128 && (!fits || n <= 256 || reuse < 3.2)));
     variant = !fast_ok ? kSddmmRowstrip
               : lane   ? kSddmmLane
               : (sizeof(T) == 4 && reuse >= 2.0 && worth && m >= 512 && fits && nnz < (1 << 29)) ? kSddmmSlabDma
