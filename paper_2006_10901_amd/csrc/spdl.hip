@@ -399,25 +399,47 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
     return;
   }
   if (variant < 0) {
-    const double reuse = (m > 0 && k > 0) ? 64.0 * (double)nnz / ((double)m * (double)k) : 0.0;
-    // wide dot products keep at most 32 nonzeros per row and 128-column slab in registers
-    // short dot products gain little from the slabs (a row of R is one or two cache lines) unless the
-    // reuse is high, and the nonzero-split kernel does not care how the entries are laid out (a
-    // banded attention mask leaves most of a panel's column ranges nearly empty)
-    const bool worth = n >= 128 || reuse >= 8.0;
-    const bool fits = n <= 128 || 128.0 * (double)nnz / ((double)m * (double)k) <= 16.0;
-    // dot products of 65..128 columns: the lane kernel, as long as a panel of 64 rows meets the
-    // same row of R at least once on average
-    // ... and longer dot products of rows too dense for the slab kernel's 32 partial sums per row and
-    // slab, in passes of 128 columns
-    // (also where the passes are few, n <= 256, or A is sparse, under 5 %: measured faster than
-    // the slab kernel there, whose stages then hold too little work for their copies)
-    const bool lane = sddmm_lane_usable<T>(n, nnz, L, R) && m >= 512 && reuse >= 1.0 &&
-                      ((n > 64 && n <= 128) || (n > 128 && (!fits || n <= 256 || reuse < 3.2)));
-    variant = !fast_ok ? kSddmmRowstrip
-              : lane   ? kSddmmLane
-              : (sizeof(T) == 4 && reuse >= 2.0 && worth && m >= 512 && fits && nnz < (1 << 29)) ? kSddmmSlabDma
-                                                                                                  : kSddmmGroup;
+    const double density = (m > 0 && k > 0) ? (double)nnz / ((double)m * (double)k) : 0.0;
+    const double reuse = 64.0 * density;
+    const bool fp32_fast = fast_ok && sizeof(T) == 4 && m >= 512 && nnz < (1 << 29) && n < (1 << 21);
+    if (!fast_ok) {
+      variant = kSddmmRowstrip;
+    } else if (n <= 128 || !fp32_fast) {
+      // Short dot products gain little from the slabs (a row of R is one or two cache lines) unless
+      // the reuse is high, and the nonzero-split kernel does not care how the entries are laid out
+      // (a banded attention mask leaves most of a panel's column ranges nearly empty).  65..128
+      // columns: the lane kernel, as long as a panel of 64 rows meets the same row of R at least
+      // once on average.
+      const bool lane = fp32_fast && n > 64 && reuse >= 1.0;
+      const bool slab = fp32_fast && reuse >= 2.0 && (n >= 128 || reuse >= 8.0);
+      variant = lane ? kSddmmLane : slab ? kSddmmSlabDma : kSddmmGroup;
+    } else {
+      // Longer dot products: three candidates, chosen by an estimate of their run times from measured
+      // rates (paper Sec. "Experiments": the kernel and tile are picked by heuristics from the shape;
+      // the discussion there names better selection as the open end).  The lane kernel runs once per
+      // 128 columns and walks A every time (about 9.5 us of fixed cost per pass); the slab kernel
+      // walks A once and keeps at most 32 partial sums per row and slab in registers, so it slows
+      // down where rows get dense; the nonzero-split kernel gathers rows of R and runs at the rate
+      // of those gathers whatever the density.  Rates in TFLOP/s against density, measured on
+      // matrices from 2048 x 2048 to 8192 x 10240 with n = 256 .. 4096.
+      static const double ds[7] = {0.01, 0.02, 0.04, 0.10, 0.16, 0.30, 0.50};
+      static const double lane_rate[7] = {5.0, 9.0, 14.0, 22.6, 26.0, 33.0, 32.0};
+      static const double slab_rate[7] = {4.0, 7.0, 12.8, 22.8, 24.0, 19.0, 12.0};
+      auto rate = [&](const double* r) {
+        if (density <= ds[0]) return r[0];
+        for (int i = 1; i < 7; ++i)
+          if (density <= ds[i]) return r[i - 1] + (r[i] - r[i - 1]) * (density - ds[i - 1]) / (ds[i] - ds[i - 1]);
+        return r[6];
+      };
+      const double flops = 2.0 * (double)nnz * (double)n;                   // per launch, all passes
+      const int passes = (n + 127) / 128;
+      const double t_lane = passes * 9.5 + flops / (rate(lane_rate) * 1e6);   // microseconds
+      const double t_slab = 8.0 + flops / (rate(slab_rate) * 1e6);
+      // (a strip of the gather kernel steps through its dot product 64 columns at a time, about 1.1 us
+      // of memory latency per step: the floor for small problems)
+      const double t_group = 5.0 + 1.1 * (double)(n / 64) + flops / 6.0e6;
+      variant = (t_lane <= t_slab && t_lane <= t_group) ? kSddmmLane : t_slab <= t_group ? kSddmmSlabDma : kSddmmGroup;
+    }
   }
   if ((variant == kSddmmSlab || variant == kSddmmSlabDma) &&
       !(fast_ok && sizeof(T) == 4 && nnz < (1 << 29) && n < (1 << 21)))   // 32-bit byte offsets

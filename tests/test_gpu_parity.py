@@ -363,8 +363,8 @@ def test_forced_sddmm_variants_ragged(g, oracle_lib, force, n):
 def test_sddmm_long_dot_products_of_dense_rows(g, oracle_lib, n):
     """Rows too dense for the slab kernel's 32 partial sums per row and slab, dot products longer
     than 128 columns: the lane kernel runs once per 128 columns and adds up in the output array.
-    Default selection on a uniform mask, ragged last chunk, rows that are not ascending (recomputed
-    as a whole, whatever the earlier passes left), and the scaled form."""
+    A uniform mask, ragged last chunk, rows that are not ascending (recomputed as a whole, whatever
+    the earlier passes left), and the scaled form."""
     import torch
     import paper_2006_10901_amd as spdl
     cases = [wl.uniform_mask_csr(1500, 1000, 0.3, 970 + n), wl.adversarial_csr(600, 300, 971 + n, sorted_cols=False)]
@@ -372,8 +372,7 @@ def test_sddmm_long_dot_products_of_dense_rows(g, oracle_lib, n):
         L, R = wl.dense(A.m, n, 972 + n), wl.dense(A.k, n, 973 + n)
         ref, S = oracle_lib.sddmm(A.m, A.k, n, A.row_offsets, A.column_indices, L, R)
         try:
-            if idx == 1:
-                spdl.spdl_force_variant(1, 5)
+            spdl.spdl_force_variant(1, 5)            # (what is chosen by default depends on the estimate of run times)
             chosen = spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"])
             assert chosen == "lane"
             g.assert_close(g.gpu_sddmm(A, L, R, n), ref, S, g.TOL_F32, f"lane sddmm in passes, n={n}")
