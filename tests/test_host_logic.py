@@ -149,6 +149,23 @@ def test_selection_uses_widest_aligned_vector(spdl):
     assert spdl.spdl_variant_name(0, 0) is not None and spdl.spdl_variant_name(0, 99) is None
 
 
+def test_sddmm_selection_for_long_dot_products(spdl):
+    """n > 128: the estimate of run times picks lane passes where rows are dense or the passes few,
+    the slab kernel where they are many and rows sparse enough, the gather kernel for very sparse A
+    (paper Sec. "Experiments": kernel selection by heuristics from the shape)."""
+    def chosen(m, k, n, density):
+        d = spdl.spdl_select_sddmm(m, k, n, int(m * k * density), 4, 0, 0)
+        return spdl.spdl_variant_name(1, d["variant"])
+    assert chosen(8192, 10240, 256, 0.50) == "lane"
+    assert chosen(8192, 10240, 512, 0.30) == "lane"
+    assert chosen(4096, 1024, 4096, 0.10) == "slabdma"          # the Transformer FFN shape
+    assert chosen(4096, 1024, 4096, 0.30) == "slabdma"          # 32 passes would cost more than the overflow
+    assert chosen(1024, 1024, 3136, 0.10) == "slabdma"          # the fp32 conv shape
+    assert chosen(1024, 1024, 1024, 0.03) == "slabdma"          # small: never 8 passes of fixed cost
+    assert chosen(8192, 10240, 256, 0.005) == "group"
+    assert chosen(300, 1024, 1024, 0.10) == "group"             # too few rows for panels of 64
+
+
 def test_forced_slab_variants_never_run_an_empty_matrix(spdl):
     """With nnz == 0 the sparse arrays and B may be null; the kernels that fetch from them
     unconditionally must not be chosen, forced or not."""
