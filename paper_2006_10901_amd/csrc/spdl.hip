@@ -107,18 +107,24 @@ int slab_rows_per_group(int m, int n) {
   return tiles128 >= 2 * kComputeUnits ? 2 : 1;
 }
 
+// Workgroups of 8 waves (panels of 32 rows, slabs of 128 rows of B, two workgroups per CU) for the
+// copy-based kernel when panels of 64 rows would leave compute units without a workgroup.
+constexpr int kSlabHalfS = 128;
+constexpr int kSlabHalfLdsBytes = 2 * (kSlabHalfS + 1) * kSlabTile * 4;
+
 void fill_spmm_slab_info(int m, int n, int variant, spdl_launch_info* info) {
-  const int rpg = variant == kSpmmSlabDma ? slab_rows_per_group(m, n) : 1;
-  const int rows = kSlabRows * rpg;
-  const int panels = (m + rows - 1) / rows;
   const int tiles = (n + kSlabTile - 1) / kSlabTile;
+  const bool half = variant == kSpmmSlabDma && (int64_t)((m + kSlabRows - 1) / kSlabRows) * tiles < kComputeUnits;
+  const int rpg = (variant == kSpmmSlabDma && !half) ? slab_rows_per_group(m, n) : 1;
+  const int rows = (half ? kSlabRows / 2 : kSlabRows) * rpg;
+  const int panels = (m + rows - 1) / rows;
   const int tpw = slab_tiles_per_wg(panels, tiles);
   const int groups = (tiles + tpw - 1) / tpw;
   info->variant = variant;
   info->vec = 4;
   info->lanes_per_row = 16;
   info->rows_per_block = rows;
-  info->block_threads = kSlabThreads;
+  info->block_threads = half ? kSlabThreads / 2 : kSlabThreads;
   info->grid_x = slab_grid_size(panels, groups);
   info->grid_y = tpw;                       // tiles walked by one workgroup (the grid is 1-D)
 }
@@ -266,19 +272,25 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const I* ci, const T*
       auto kernel = spmm_slab_kernel<T, kSlabS>;
       // 32 pairs fetched ahead per row.  Deeper look-ahead (4 or 6 chunks of 16) was measured
       // on the 70-90 % sparse shapes: the longer scan per round costs more than the waits it saves.
-      const bool two_rows = li.rows_per_block != kSlabRows;
-      const void* dma_kernel = two_rows ? (const void*)spmm_slab_dma_kernel<kSlabS, 2, 2>
-                                        : (const void*)spmm_slab_dma_kernel<kSlabS, 1, 2>;
+      const bool half = li.block_threads != kSlabThreads;
+      const bool two_rows = li.rows_per_block == 2 * kSlabRows;
+      const void* dma_kernel = half       ? (const void*)spmm_slab_dma_kernel<kSlabHalfS, 1, 2, 8>
+                               : two_rows ? (const void*)spmm_slab_dma_kernel<kSlabS, 2, 2>
+                                          : (const void*)spmm_slab_dma_kernel<kSlabS, 1, 2>;
+      const int lds = half ? kSlabHalfLdsBytes : kSlabLdsBytes;
       if (!configured.load()) {
         for (const void* f : {(const void*)kernel, (const void*)spmm_slab_dma_kernel<kSlabS, 1, 2>,
                               (const void*)spmm_slab_dma_kernel<kSlabS, 2, 2>})
           if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kSlabLdsBytes) != hipSuccess)
             return SPDL_ERR_LAUNCH;
+        if (hipFuncSetAttribute((const void*)spmm_slab_dma_kernel<kSlabHalfS, 1, 2, 8>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSlabHalfLdsBytes) != hipSuccess)
+          return SPDL_ERR_LAUNCH;
         configured.store(true);
       }
       const int panels = (m + li.rows_per_block - 1) / li.rows_per_block;
       const int tiles = (n + kSlabTile - 1) / kSlabTile;
-      const dim3 grid(li.grid_x), block(kSlabThreads);
+      const dim3 grid(li.grid_x), block(li.block_threads);
       if (li.variant == kSpmmSlab) {
         kernel<<<grid, block, kSlabLdsBytes, st>>>(m, k, n, nnz, tiles, li.grid_y, panels, ro, ci, val, order, B, C,
                                                    bias, relu);
@@ -286,7 +298,7 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const I* ci, const T*
         int tpw = li.grid_y;
         void* args[] = {&m, &k, &n, &nnz, (void*)&tiles, &tpw, (void*)&panels, &ro, &ci, &val, &order, &B, &C,
                         &bias, &relu};
-        if (hipLaunchKernel(dma_kernel, grid, block, args, kSlabLdsBytes, st) != hipSuccess) return SPDL_ERR_LAUNCH;
+        if (hipLaunchKernel(dma_kernel, grid, block, args, lds, st) != hipSuccess) return SPDL_ERR_LAUNCH;
       }
     } else {
       return SPDL_ERR_UNSUPPORTED;

@@ -23,8 +23,11 @@ namespace spdl {
 // enough tiles to fill the machine anyway.
 // NCH = chunks of 16 pairs fetched ahead per row (chosen by the host from the density so that
 // a row's pairs inside one slab usually fit).
-template <int S, int RPG, int NCH>
-__global__ __launch_bounds__(kSlabThreads) void spmm_slab_dma_kernel(
+// NW = waves per workgroup: 16 (one workgroup per CU), or 8 with slabs half as large, so that two
+// workgroups share a CU: panels of 32*RPG rows, for outputs with fewer than 256 tiles of 64 x 64,
+// which would otherwise leave compute units without a workgroup.
+template <int S, int RPG, int NCH, int NW = 16>
+__global__ __launch_bounds__(64 * NW) void spmm_slab_dma_kernel(
     int m, int k, int n, int nnz, int tiles_n, int tiles_per_wg, int panels,
     const int* __restrict__ row_offsets, const int* __restrict__ column_indices,
     const float* __restrict__ values, const int* __restrict__ row_order, const float* __restrict__ B,
@@ -33,7 +36,7 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_dma_kernel(
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
   constexpr int kBufBytes = (S + 1) * kSlabTile * 4;      // S data rows + one all-zero row
   constexpr int kZeroOff = S * kSlabTile * 4;
-  constexpr int kCopies = S / 64;                         // 1 KB direct-to-LDS loads per wave per slab
+  constexpr int kCopies = S / (4 * NW);                   // 1 KB direct-to-LDS loads per wave per slab
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -53,7 +56,7 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_dma_kernel(
   if (tid < 2 * kSlabTile)
     *reinterpret_cast<float*>(lds_raw + (tid >> 6) * kBufBytes + kZeroOff + (tid & 63) * 4) = 0.f;
 
-  // Slab copy: copy i of wave w fills slab rows (i*16 + w)*4 .. +3; lane L brings row L/16 of
+  // Slab copy: copy i of wave w fills slab rows (i*NW + w)*4 .. +3; lane L brings row L/16 of
   // those, columns 4*(L%16) .. +3, and the hardware places lane L's 16 bytes at M0 + 16*L.
   // The address is a scalar base (start of the slab in B, moved from stage to stage with scalar
   // arithmetic) plus a per-lane byte offset that is the same in every stage except a ragged
@@ -64,7 +67,7 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_dma_kernel(
   const int last_rows = k - (nslabs - 1) * S;               // rows of the last slab, 1..S
 #pragma unroll
   for (int i = 0; i < kCopies; ++i) {
-    const int lrow = (i * 16 + wave) * 4 + sub;
+    const int lrow = (i * NW + wave) * 4 + sub;
     row_off[i] = (unsigned)lrow * (unsigned)n * 4u;
     row_off_last[i] = (unsigned)min(lrow, last_rows - 1) * (unsigned)n * 4u;
   }
@@ -86,7 +89,7 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_dma_kernel(
 #pragma unroll
     for (int i = 0; i < kCopies; ++i) {
       const unsigned voff = (last ? row_off_last[i] : row_off[i]) + col_off;
-      const unsigned m0v = dst + (unsigned)i * (16 * 4 * kSlabTile * 4);
+      const unsigned m0v = dst + (unsigned)i * (NW * 4 * kSlabTile * 4);
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                    :: "s"(m0v), "v"(voff), "s"(base) : "memory", "m0");
     }
