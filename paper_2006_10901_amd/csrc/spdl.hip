@@ -135,9 +135,27 @@ void fill_spmm_slab_info(int m, int n, int variant, spdl_launch_info* info) {
 constexpr int kSpmmMfmaWaves = 2;                 // 256-column tiles per workgroup of the MFMA kernel
 constexpr int kSpmmMfmaKParts = 2;                // waves per tile, splitting the contraction
 
-// The matrix-core kernels (fp16 only) do dense work on 32-row panels / 32x32 blocks: worth it
-// when at least one position in 32 is stored.
-inline bool mfma_dense_enough(int m, int k, int nnz) { return 32.0 * (double)nnz >= (double)m * (double)k; }
+// The matrix-core kernels (fp16 only) do dense work on 32-row panels / 64x64 blocks: selected
+// when an estimate of their run time is below that of the direct kernel (microseconds, from
+// measured rates on shapes from 1024 x 1024 x 3136 to 8192 x 10240 x 128).  The matrix-core kernels
+// do work proportional to m*k whatever the density, in rounds of one workgroup per CU: a panel of
+// 32 rows x 512 columns costs about 8.4 us plus 13.8 ns per column of A (SpMM), a 64 x 64 block
+// 3.5 us plus 0.5 us per 128 columns of the dot product (SDDMM); filling the panels and sampling
+// the blocks add 24 and 8 us per million entries.  The direct kernels run at the rate of their
+// gathers: 19.5 TFLOP/s (SpMM); 14 TFLOP/s for short dot products, 8 beyond 128 columns, after a
+// latency floor of 2 us per 64 columns of the dot product (SDDMM).
+inline bool spmm_mfma_pays(int m, int k, int n, int nnz) {
+  const double wgs = (double)((m + 31) / 32) * (double)(((n + 255) / 256 + kSpmmMfmaWaves - 1) / kSpmmMfmaWaves);
+  const double t_mfma = std::ceil(wgs / kComputeUnits) * (8.4 + 0.0138 * (double)k) + 24e-6 * (double)nnz;
+  const double t_direct = 7.0 + 2.0 * (double)nnz * (double)n / 19.5e6;
+  return t_mfma <= t_direct;
+}
+inline bool sddmm_mfma_pays(int m, int k, int n, int nnz) {
+  const double blocks = (double)((m + 63) / 64) * (double)((k + 63) / 64);
+  const double t_mfma = std::ceil(blocks / kComputeUnits) * (3.5 + 0.5 * (double)((n + 127) / 128)) + 8e-6 * (double)nnz;
+  const double t_direct = 5.0 + 2.0 * (double)(n / 64) + 2.0 * (double)nnz * (double)n / ((n <= 128 ? 14.0 : 8.0) * 1e6);
+  return t_mfma <= t_direct;
+}
 
 // The matrix-core SpMM keeps rows of B in registers whose loads are still in flight (explicit
 // waits); a register spilled inside that window would be copied before its data has arrived.
@@ -165,7 +183,8 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
   // fetch from them unconditionally; the row-splitting kernel only writes the zeros of C
   if (nnz == 0 && (variant == kSpmmMfma || variant == kSpmmSlab || variant == kSpmmSlabDma)) variant = kSpmmRowsplit;
   if (variant == kSpmmMfma && (!mfma_ok || !spmm_mfma_runnable())) variant = kSpmmRowsplit;
-  if (variant < 0 && mfma_ok && nnz > 0 && mfma_dense_enough(m, k, nnz) && spmm_mfma_runnable()) variant = kSpmmMfma;
+  if (variant < 0 && mfma_ok && nnz > 0 && spmm_mfma_pays(m, k, n, nnz) && spmm_mfma_runnable())
+    variant = kSpmmMfma;
   if (variant == kSpmmMfma) {
     // 32-row panels, kSpmmMfmaWaves tiles per workgroup.  (64-row panels, which would halve the
     // reads of B, need 256 accumulator registers per lane; the compiler then spills in the main
@@ -397,7 +416,7 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
   const bool mfma_ok = sizeof(T) == 2 && n > 0 && n % 8 == 0 && aligned(L, 16) && aligned(R, 16) &&
                        (int64_t)((m + 63) / 64) * ((k + 63) / 64) < ((int64_t)1 << 31);
   if (variant == kSddmmMfma && !mfma_ok) variant = kSddmmGroup;
-  if (variant < 0 && mfma_ok && mfma_dense_enough(m, k, nnz)) variant = kSddmmMfma;
+  if (variant < 0 && mfma_ok && sddmm_mfma_pays(m, k, n, nnz)) variant = kSddmmMfma;
   if (variant == kSddmmMfma) {
     const int64_t tiles = (int64_t)((m + 63) / 64) * ((k + 63) / 64);
     info->variant = kSddmmMfma;

@@ -458,9 +458,11 @@ def test_mfma_kernels_are_the_default_for_moderately_sparse_fp16(g):
     import paper_2006_10901_amd as spdl
     assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(1024, 1024, 3136, 104000, 2, 0, 0)["variant"]) == "mfma"
     assert spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(1024, 1024, 3136, 104000, 2, 0, 0)["variant"]) == "mfma"
-    # one stored position in a hundred: gathers are cheaper than dense blocks
+    # one stored position in a hundred: gathering rows of B is cheaper than dense panels (SpMM); for SDDMM the
+    # dense blocks stay cheaper at this length of the dot products, but not for short ones
     assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(1024, 1024, 3136, 10400, 2, 0, 0)["variant"]) == "rowsplit"
-    assert spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(1024, 1024, 3136, 10400, 2, 0, 0)["variant"]) == "group"
+    assert spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(1024, 1024, 3136, 10400, 2, 0, 0)["variant"]) == "mfma"
+    assert spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(2048, 2048, 64, 41000, 2, 0, 0)["variant"]) == "group"
     # fp32 never takes them, n % 8 != 0 neither
     assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(1024, 1024, 3136, 104000, 4, 0, 0)["variant"]) != "mfma"
     assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(1024, 1024, 3132, 104000, 2, 0, 0)["variant"]) == "rowsplit"

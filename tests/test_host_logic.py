@@ -138,10 +138,15 @@ def test_selection_uses_widest_aligned_vector(spdl):
     assert spdl.spdl_variant_name(1, d["variant"]) == "slabdma"
     d = spdl.spdl_select_sddmm(8192, 10240, 130, 8 << 20, 4, 0, 0)           # n % 4 != 0: general kernel
     assert spdl.spdl_variant_name(1, d["variant"]) == "rowstrip" and d["block_threads"] == 256
-    d = spdl.spdl_select_sddmm(1024, 1024, 3136, 20000, 2, 0, 0)             # sparse fp16: strip kernel
+    d = spdl.spdl_select_sddmm(2048, 2048, 64, 20000, 2, 0, 0)               # sparse fp16, short dot products: strip kernel
     # split by nonzeros: waves of 64 entries each, 4 waves per block
     assert spdl.spdl_variant_name(1, d["variant"]) == "group" and d["rows_per_block"] == 64
     assert d["grid_x"] == (20000 + 255) // 256
+    # (with long dot products the gather kernel's latency per strip makes the dense blocks cheaper even at 2 %)
+    assert spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(1024, 1024, 3136, 20000, 2, 0, 0)["variant"]) == "mfma"
+    # the LSTM shape in fp16: 20480 blocks of 64 x 64 for 128 columns each cost more than gathering
+    assert spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(8192, 10240, 128, 8 << 20, 2, 0, 0)["variant"]) == "group"
+    assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(8192, 10240, 128, 8 << 20, 2, 0, 0)["variant"]) == "rowsplit"
     d = spdl.spdl_select_sddmm(1024, 1024, 3136, 100000, 2, 0, 0)            # one position in ten: dense blocks
     assert spdl.spdl_variant_name(1, d["variant"]) == "mfma" and d["grid_x"] == 8 * 8 * 4
     s = spdl.spdl_select_spmm(1024, 1024, 3136, 100000, 2, 0, 0)
