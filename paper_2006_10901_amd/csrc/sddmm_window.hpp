@@ -1,0 +1,111 @@
+// SDDMM, window family: the counterpart of the window SpMM kernel for sparse matrices whose
+// entries cluster around a band (the attention masks of paper Sec. "Application: Sparse
+// Transformer") and dot products of at most 64 columns (one attention head).  A workgroup owns
+// NW consecutive sparse rows, one per wave, and copies ONE window of 256 consecutive rows of R
+// into LDS, placed where its rows have most of their entries.  A row is cut into strips of 16
+// consecutive entries, dealt to the wave's four 16-lane groups; a strip whose 16 columns all lie
+// inside the window reads its rows of R from LDS, any other strip gathers them from global
+// memory exactly as the nonzero-split kernel does.  The arithmetic of a strip is that kernel's
+// (four columns of the dot product per lane, one partial sum per entry, a transposing reduction
+// that leaves entry t's result in lane t), so both give the same bits.
+// Any CSR input gives the right result; the window's position is only a matter of speed.
+// Needs n <= 64, n % 4 == 0, 16-byte aligned L and R, k * n < 2^29.
+#pragma once
+#include "common.hpp"
+#include "sddmm_group.hpp"
+#include "spmm_window.hpp"
+
+namespace spdl {
+
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void sddmm_window_kernel(
+    int m, int k, int n, int nnz, const int* __restrict__ row_offsets,
+    const int* __restrict__ column_indices, const float* __restrict__ L, const float* __restrict__ R,
+    float* __restrict__ out, const float* __restrict__ scale) {
+  constexpr int W = 256;
+  constexpr int kCopies = W / (4 * NW);
+  static_assert(W % (4 * NW) == 0, "every wave copies the same number of 4-row pieces");
+  extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = uniform(tid >> 6);
+  const int sub = lane >> 4;
+  const int l16 = lane & 15;
+  const int col = l16 * 4;
+  const bool col_ok = col < n;
+  const int lane_b = col_ok ? l16 * 16 : 0;
+
+  const int r0 = blockIdx.x * NW;
+  const int r1 = min(m, r0 + NW) - 1;
+  const int c0 = win_place<W>(row_offsets, column_indices, r0, r1, k);
+
+  // The window copy: copy i of wave w fills window rows (i*NW + w)*4 .. +3 (256 bytes each in
+  // LDS), lane L row L/16 of those and columns 4*(L%16) .. +3; rows past k are clamped to row
+  // k-1 and columns past n to column 0 (nothing valid reads those).
+  if (c0 < k) {
+    const char* base = reinterpret_cast<const char*>(R);
+    const unsigned dst = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds_raw +
+                         (unsigned)wave * (4 * 64 * 4);
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i) {
+      const int lrow = (i * NW + wave) * 4 + sub;
+      const unsigned voff = (unsigned)min(c0 + lrow, k - 1) * (unsigned)n * 4u + (unsigned)lane_b;
+      const unsigned m0v = dst + (unsigned)i * (NW * 4 * 64 * 4);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :: "s"(m0v), "v"(voff), "s"(base) : "memory", "m0");
+    }
+  }
+
+  const int row = r0 + wave;
+  const bool row_ok = row < m;
+  const int p_begin = row_ok ? row_offsets[row] : 0;
+  const int p_end = row_ok ? row_offsets[row + 1] : 0;
+  const float* Lrow = L + (size_t)(row_ok ? row : 0) * n;
+  float l[4];
+  Pack<float, 4>::load(Lrow + (col_ok ? col : 0), l);
+#pragma unroll
+  for (int v = 0; v < 4; ++v) l[v] = col_ok ? l[v] : 0.f;
+
+  // the column of this lane's entry of the strip at `at`; past the row end the last entry's again
+  auto fetch = [&](int at) { return column_indices[max(min(at + l16, p_end - 1), 0)]; };
+  int at = p_begin + 16 * sub;
+  int cc = fetch(at);
+
+  __builtin_amdgcn_s_waitcnt(0);      // the window copy
+  __syncthreads();
+
+  for (; __any(at < p_end); at += 64) {
+    const int cn = fetch(at + 64);
+    const unsigned rel = (unsigned)(cc - c0);
+    const unsigned long long m_in = __builtin_amdgcn_ballot_w64(rel < (unsigned)W);
+    const bool group_in = ((unsigned)(m_in >> (16 * sub)) & 0xffffu) == 0xffffu;
+    if (at < p_end) {
+      if (group_in) {
+        const int off = (int)(rel * 256u);
+        f32x4 r[16];
+#define SPDL_W1(T0) \
+        r[T0] = *reinterpret_cast<const f32x4*>(lds_raw + (__builtin_amdgcn_update_dpp(0, off, 0x150 + (T0), 0xf, 0xf, false) + lane_b));
+        SPDL_W1(0) SPDL_W1(1) SPDL_W1(2) SPDL_W1(3) SPDL_W1(4) SPDL_W1(5) SPDL_W1(6) SPDL_W1(7)
+        SPDL_W1(8) SPDL_W1(9) SPDL_W1(10) SPDL_W1(11) SPDL_W1(12) SPDL_W1(13) SPDL_W1(14) SPDL_W1(15)
+#undef SPDL_W1
+        float partial[16];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+          partial[t] = 0.f;
+          partial[t] = __builtin_fmaf(l[0], r[t].x, partial[t]);
+          partial[t] = __builtin_fmaf(l[1], r[t].y, partial[t]);
+          partial[t] = __builtin_fmaf(l[2], r[t].z, partial[t]);
+          partial[t] = __builtin_fmaf(l[3], r[t].w, partial[t]);
+        }
+        const float total = reduce16x16(partial, l16);
+        if (at + l16 < p_end) sddmm_store<float>(out, scale, at + l16, total);
+      } else {
+        sddmm_strip_direct_at<float>(n, at, p_end, l16, cc * n, Lrow, R, out, scale);
+      }
+    }
+    cc = cn;
+  }
+}
+
+}  // namespace spdl

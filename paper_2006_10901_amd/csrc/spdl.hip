@@ -23,13 +23,15 @@
 #include "spmm_slab.hpp"
 #include "spmm_mfma.hpp"
 #include "spmm_slab_dma.hpp"
+#include "spmm_window.hpp"
+#include "sddmm_window.hpp"
 
 namespace {
 
 using namespace spdl;
 
-enum SpmmVariant { kSpmmRowsplit = 0, kSpmmSlab = 1, kSpmmSlabDma = 2, kSpmmMfma = 3, kSpmmVariants };
-enum SddmmVariant { kSddmmRowstrip = 0, kSddmmGroup = 1, kSddmmSlab = 2, kSddmmSlabDma = 3, kSddmmMfma = 4, kSddmmLane = 5, kSddmmVariants };
+enum SpmmVariant { kSpmmRowsplit = 0, kSpmmSlab = 1, kSpmmSlabDma = 2, kSpmmMfma = 3, kSpmmWindow = 4, kSpmmVariants };
+enum SddmmVariant { kSddmmRowstrip = 0, kSddmmGroup = 1, kSddmmSlab = 2, kSddmmSlabDma = 3, kSddmmMfma = 4, kSddmmLane = 5, kSddmmWindow = 6, kSddmmVariants };
 
 std::atomic<int> g_forced[2] = {{-1}, {-1}};
 
@@ -132,6 +134,7 @@ void fill_spmm_slab_info(int m, int n, int variant, spdl_launch_info* info) {
 // Kernel selection (paper Sec. "Experiments": tile and vector width from the problem shape).
 // The slab kernel re-reads each B row from LDS once per sparse row that uses it, so it pays
 // when a 64-row panel touches the same B row several times: 64 * density >= 2.
+constexpr int kWinWaves = 16;                     // waves per workgroup of the window kernel, one sparse row each
 constexpr int kSpmmMfmaWaves = 2;                 // 256-column tiles per workgroup of the MFMA kernel
 constexpr int kSpmmMfmaKParts = 2;                // waves per tile, splitting the contraction
 
@@ -206,8 +209,28 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
     const int64_t out_tiles = (int64_t)((m + kSlabRows - 1) / kSlabRows) * ((n + kSlabTile - 1) / kSlabTile);
     variant = (sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) && reuse >= 2.0 && out_tiles >= kComputeUnits / 2)
                   ? kSpmmSlabDma : kSpmmRowsplit;
+    // One 64-column tile, rows of a few hundred entries, at most 1/8 dense: the shape of an
+    // attention head (paper Sec. "Application: Sparse Transformer").  The host cannot see whether
+    // the entries form a band; the window kernel is chosen because it is the fastest of the three
+    // when they do (sequence 4096 .. 12288, band 256: 1.2 .. 1.3 times the row-splitting kernel
+    // and 2.2 .. 2.6 times the slab kernel, which walks every slab of B for a handful of entries)
+    // and within 15 % of the best when they do not (its gathers are the row-splitting kernel's).
+    // Narrower outputs leave its lanes idle, fewer rows leave it too few waves, and denser or
+    // wider problems without a band belong to the slab kernel.
+    if (sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) && (int64_t)k * n < ((int64_t)1 << 29) && n > 32 &&
+        n <= kWinTile && m >= 4096 && (double)nnz >= 192.0 * (double)m && (double)nnz <= 0.125 * (double)m * (double)k)
+      variant = kSpmmWindow;
   }
-  if ((variant == kSpmmSlab || variant == kSpmmSlabDma) && sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C)) {
+  if (variant == kSpmmWindow && sizeof(T) == 4 && nnz > 0 && slab_usable<T>(n, nnz, B, C) &&
+      (int64_t)k * n < ((int64_t)1 << 29)) {
+    info->variant = kSpmmWindow;
+    info->vec = 4;
+    info->lanes_per_row = 16;
+    info->rows_per_block = WinShape<kWinWaves>::kRows;
+    info->block_threads = 64 * kWinWaves;
+    info->grid_x = (m + info->rows_per_block - 1) / info->rows_per_block;
+    info->grid_y = (n + kWinTile - 1) / kWinTile;
+  } else if ((variant == kSpmmSlab || variant == kSpmmSlabDma) && sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C)) {
     fill_spmm_slab_info(m, n, variant, info);
   } else {
     fill_spmm_rowsplit_info<T>(m, n, nnz, B, C, info);
@@ -282,6 +305,21 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const I* ci, const T*
       }
       kernel<<<dim3(li.grid_x), dim3(li.block_threads), spmm_mfma_lds_bytes(k, kSpmmMfmaWaves, 1), st>>>(
           m, k, n, li.grid_y, ro, ci, val, B, C, bias, relu);
+    } else {
+      return SPDL_ERR_UNSUPPORTED;
+    }
+  } else if (li.variant == kSpmmWindow) {
+    if constexpr (sizeof(T) == 4 && kInt32) {
+      static std::atomic<bool> configured{false};
+      auto kernel = spmm_window_kernel<kWinWaves>;
+      constexpr int lds = WinShape<kWinWaves>::kLdsBytes;
+      if (!configured.load()) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
+            hipSuccess)
+          return SPDL_ERR_LAUNCH;
+        configured.store(true);
+      }
+      kernel<<<dim3(li.grid_x, li.grid_y), dim3(li.block_threads), lds, st>>>(m, k, n, nnz, ro, ci, val, B, C, bias, relu);
     } else {
       return SPDL_ERR_UNSUPPORTED;
     }
@@ -444,6 +482,14 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
       const bool lane = fp32_fast && n > 64 && reuse >= 1.0;
       const bool slab = fp32_fast && reuse >= 2.0 && (n >= 128 || reuse >= 8.0);
       variant = lane ? kSddmmLane : slab ? kSddmmSlabDma : kSddmmGroup;
+      // The shape of an attention head (33..64 columns, thousands of rows of a few hundred entries,
+      // at most 1/8 dense; paper Sec. "Application: Sparse Transformer"): the window kernel, which is
+      // the nonzero-split kernel with the rows of R around a band taken from LDS (13 % faster on a
+      // band of 256 at sequence 4096, 2 .. 10 % on uniform masks of that shape).
+      if (variant == kSddmmGroup && fp32_fast && n > 32 && n <= kWinTile && m >= 4096 && aligned(L, 16) &&
+          aligned(R, 16) && (int64_t)k * n < ((int64_t)1 << 29) && (double)nnz >= 192.0 * (double)m &&
+          (double)nnz <= 0.125 * (double)m * (double)k)
+        variant = kSddmmWindow;
     } else {
       // Longer dot products: three candidates, chosen by an estimate of their run times from measured
       // rates (paper Sec. "Experiments": the kernel and tile are picked by heuristics from the shape;
@@ -476,11 +522,22 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
       !(fast_ok && sizeof(T) == 4 && nnz < (1 << 29) && n < (1 << 21)))   // 32-bit byte offsets
     variant = kSddmmGroup;
   if (variant == kSddmmLane && !sddmm_lane_usable<T>(n, nnz, L, R)) variant = kSddmmGroup;
+  if (variant == kSddmmWindow && !(sizeof(T) == 4 && fast_ok && aligned(L, 16) && aligned(R, 16) && n <= kWinTile &&
+                                   nnz > 0 && (int64_t)k * n < ((int64_t)1 << 29)))
+    variant = kSddmmGroup;
   if (variant == kSddmmGroup && !fast_ok) variant = kSddmmRowstrip;
   const int avg = m > 0 ? nnz / m : 0;
   info->variant = variant;
   info->block_threads = 256;
   info->grid_y = 1;
+  if (variant == kSddmmWindow) {
+    info->vec = 4;
+    info->lanes_per_row = 16;
+    info->rows_per_block = kWinWaves;
+    info->block_threads = 64 * kWinWaves;
+    info->grid_x = (m + kWinWaves - 1) / kWinWaves;
+    return;
+  }
   if (variant == kSddmmLane) {
     const SddmmLaneShape sh = sddmm_lane_shape(m, k, nnz, n > 128);
     info->vec = 8;
@@ -616,6 +673,23 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
       else if (sh.U == 1) rc = launch_sddmm_slab<T, 1, 256, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma, order);
       else rc = launch_sddmm_slab<T, 2, 128, false>(sh, li.grid_x, m, k, n, nnz, ro, ci, L, R, out, scale, st, dma, order);
       if (rc != SPDL_OK) return rc;
+      return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
+    } else {
+      return SPDL_ERR_UNSUPPORTED;
+    }
+  }
+  if (li.variant == kSddmmWindow) {
+    if constexpr (sizeof(T) == 4) {
+      static std::atomic<bool> configured{false};
+      auto kernel = sddmm_window_kernel<kWinWaves>;
+      constexpr int lds = 256 * 64 * 4;
+      if (!configured.load()) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
+            hipSuccess)
+          return SPDL_ERR_LAUNCH;
+        configured.store(true);
+      }
+      kernel<<<dim3(li.grid_x), dim3(li.block_threads), lds, st>>>(m, k, n, nnz, ro, ci, L, R, out, scale);
       return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
     } else {
       return SPDL_ERR_UNSUPPORTED;
@@ -866,8 +940,8 @@ int spdl_force_variant(int op, int variant) {
 }
 
 const char* spdl_variant_name(int op, int variant) {
-  static const char* const spmm[] = {"rowsplit", "slab", "slabdma", "mfma"};
-  static const char* const sddmm[] = {"rowstrip", "group", "slab", "slabdma", "mfma", "lane"};
+  static const char* const spmm[] = {"rowsplit", "slab", "slabdma", "mfma", "window"};
+  static const char* const sddmm[] = {"rowstrip", "group", "slab", "slabdma", "mfma", "lane", "window"};
   if (op == 0 && variant >= 0 && variant < kSpmmVariants) return spmm[variant];
   if (op == 1 && variant >= 0 && variant < kSddmmVariants) return sddmm[variant];
   return nullptr;

@@ -312,6 +312,18 @@ __global__ __launch_bounds__(kSlabThreads) void spmm_slab_kernel(
   }
 }
 
+// The sixteen multiply-adds of pairs 4Q .. 4Q+3 of every group as functions, for kernels that
+// bring the rows of B in some other way (bq[j] = the four columns of this lane in the row of B of
+// pair 4Q+j; av = the group's values, lane t holding pair t).
+#define SPDL_DEF_FMA16(NAME, T0, T1, T2, T3)                                                      \
+  __device__ __forceinline__ void NAME(float (&acc)[4], float av, const f32x4 (&bq)[4]) {          \
+    SPDL_DPP_FMA16(bq, T0, T1, T2, T3, "s_nop 1\n\t")                                             \
+  }
+SPDL_DEF_FMA16(slab_fma16_q0, 0, 1, 2, 3)
+SPDL_DEF_FMA16(slab_fma16_q1, 4, 5, 6, 7)
+SPDL_DEF_FMA16(slab_fma16_q2, 8, 9, 10, 11)
+SPDL_DEF_FMA16(slab_fma16_q3, 12, 13, 14, 15)
+#undef SPDL_DEF_FMA16
 #undef SPDL_DPP_FMA16
 #undef SPDL_DPP_LOAD4
 #undef SPDL_DPP_ADDR

@@ -147,3 +147,32 @@ def test_sddmm_every_family_contains_nonfinite_rows_of_L_and_R(g, oracle_lib, fo
             continue                                    # fp32 only: a forced choice falls back
         force(1, v)
         same_where_finite(g.gpu_sddmm(A, L, R, n), out, S, tol, atol, f"sddmm {name} {dtype.__name__}")
+
+
+def test_window_kernels_contain_nonfinite_rows_inside_and_outside_the_window(g, oracle_lib, force):
+    """A banded mask, 64 columns: one non-finite row of the dense operand sits inside the band of the
+    rows that reference it (it reaches them through the window in LDS), one far from the diagonal
+    (gathered); rows that reference neither stay finite and right."""
+    import paper_2006_10901_amd as spdl
+    A = wl.banded_attention_csr(640, 128, 0.3, 4300)
+    n = 64
+    B, L = wl.dense(A.k, n, 4301), wl.dense(A.m, n, 4302)
+    L[L == 0] = 1
+    B[300, 0] = np.inf
+    B[300, 7] = np.nan
+    B[10, 63] = -np.inf
+    touched = np.array([np.isin([300, 10], A.column_indices[A.row_offsets[i]:A.row_offsets[i + 1]]).any()
+                        for i in range(A.m)])
+    assert touched[300] and 100 < touched.sum() < A.m - 100
+    with np.errstate(invalid="ignore", over="ignore"):
+        C, S = oracle_lib.spmm(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, B)
+        out, So = oracle_lib.sddmm(A.m, A.k, n, A.row_offsets, A.column_indices, L, B)
+    assert np.all(np.isfinite(C[~touched])) and not np.all(np.isfinite(C[touched]))
+    by0, by1 = dict((nm, v) for v, nm in variants(0)), dict((nm, v) for v, nm in variants(1))
+    force(0, by0["window"])
+    assert spdl.spdl_select_spmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"] == by0["window"]
+    same_where_finite(g.gpu_spmm(A, B, n, None), C, S, g.TOL_F32, 0.0, "spmm window")
+    force(1, by1["window"])
+    assert spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"] == by1["window"]
+    same_where_finite(g.gpu_sddmm(A, L, B, n), out, So, g.TOL_F32, 0.0, "sddmm window")
+

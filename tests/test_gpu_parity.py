@@ -308,8 +308,10 @@ def test_forced_spmm_variants_ragged(g, oracle_lib, force, n):
         assert sel["variant"] == v
         got = g.gpu_spmm(A, B, n, order)
         g.assert_close(got, C, S, g.TOL_F32, f"variant {spdl.spdl_variant_name(0, v)} n={n}")
-        # (when several lane groups share a row, the row-splitting kernel adds partial sums)
-        if sel["block_threads"] != 256 or sel["rows_per_block"] * sel["lanes_per_row"] == 256:
+        # (when several lane groups share a row, the row-splitting kernel adds partial sums, and
+        # the window kernel always does)
+        if spdl.spdl_variant_name(0, v) != "window" and (
+                sel["block_threads"] != 256 or sel["rows_per_block"] * sel["lanes_per_row"] == 256):
             results.append(got)
     # every family adds a row's products in stored order with fused multiply-adds: same bits
     assert len(results) >= 2
@@ -353,8 +355,10 @@ def test_forced_sddmm_variants_ragged(g, oracle_lib, force, n):
                 continue                                  # fp16 only, see the mixed-precision tests
             force(1, v)
             chosen = spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"])
-            # (the lane kernel takes dot products of more than 128 columns in passes of 128)
-            assert chosen == spdl.spdl_variant_name(1, v)
+            # (the lane kernel takes dot products of more than 128 columns in passes of 128; the window
+            # kernel is for dot products of at most 64 columns)
+            name = spdl.spdl_variant_name(1, v)
+            assert chosen == ("group" if name == "window" and n > 64 else name)
             got = g.gpu_sddmm(A, L, R, n)
             g.assert_close(got, out, S, g.TOL_F32, f"sddmm variant {spdl.spdl_variant_name(1, v)} n={n}")
 
@@ -397,6 +401,36 @@ def test_forced_sddmm_variants_fp16_and_long_rows(g, oracle_lib, force):
             force(1, v)
             got = g.gpu_sddmm(A, L, R, n)
             g.assert_close(got, out, S, tol, f"sddmm variant {spdl.spdl_variant_name(1, v)} {dt.__name__}")
+
+
+@pytest.mark.parametrize("n", [36, 64])
+def test_window_kernels_on_banded_masks(g, oracle_lib, force, n):
+    """The window kernels (one window of 256 rows of the dense operand in LDS per 16 sparse rows,
+    gathers for the rest) on masks with a band: a row count that is not a multiple of 16, fewer
+    columns than a window holds, a band that is not on the diagonal of a rectangular matrix, and a
+    uniform mask, for which no window is placed.  SDDMM gives the bits of the nonzero-split kernel."""
+    import paper_2006_10901_amd as spdl
+    v0 = {spdl.spdl_variant_name(0, v): v for v in spmm_variants()}
+    v1 = {spdl.spdl_variant_name(1, v): v for v in sddmm_variants()}
+    shifted = wl.banded_attention_csr(600, 128, 0.3, 2105 + n)
+    shifted = wl.Csr(600, 1500, shifted.row_offsets, (shifted.column_indices + 700).astype(np.int32), shifted.values)
+    cases = [wl.banded_attention_csr(1000, 128, 0.2, 2100 + n), wl.banded_attention_csr(200, 64, 0.5, 2101 + n),
+             shifted, wl.uniform_mask_csr(500, 3000, 0.1, 2102 + n)]
+    for idx, A in enumerate(cases):
+        B, L = wl.dense(A.k, n, 2103 + n), wl.dense(A.m, n, 2104 + n)
+        C, S = oracle_lib.spmm(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, B)
+        force(0, v0["window"])
+        assert spdl.spdl_select_spmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"] == v0["window"]
+        g.assert_close(g.gpu_spmm(A, B, n, None), C, S, g.TOL_F32, f"window spmm case {idx} n={n}")
+        out, So = oracle_lib.sddmm(A.m, A.k, n, A.row_offsets, A.column_indices, L, B)
+        force(1, v1["window"])
+        assert spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"] == v1["window"]
+        got = g.gpu_sddmm(A, L, B, n)
+        g.assert_close(got, out, So, g.TOL_F32, f"window sddmm case {idx} n={n}")
+        force(1, v1["group"])
+        assert np.array_equal(got, g.gpu_sddmm(A, L, B, n))
+        force(0, -1)
+        force(1, -1)
 
 
 # ------------------------------------------------------------------ matrix-core kernels (fp16)

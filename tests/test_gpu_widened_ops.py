@@ -161,7 +161,8 @@ def test_bias_relu_every_variant(g, oracle_lib, force, n):
             g.assert_close(got, C, S, g.TOL_F32, f"{spdl.spdl_variant_name(0, v)} bias={b is not None} relu={relu}")
             if relu:
                 assert (got >= 0).all() and (got == 0).any()
-            results.append(got)
+            if spdl.spdl_variant_name(0, v) != "window":         # (adds four partial sums per row)
+                results.append(got)
         for r in results[1:]:
             assert np.array_equal(r, results[0])
         force(0, -1)

@@ -171,11 +171,51 @@ def test_sddmm_selection_for_long_dot_products(spdl):
     assert chosen(300, 1024, 1024, 0.10) == "group"             # too few rows for panels of 64
 
 
+def test_spmm_selection_of_the_window_kernel(spdl):
+    """One 64-column tile, a few hundred entries per row, at most 1/8 dense, thousands of rows: the
+    shape of an attention head (paper Sec. "Application: Sparse Transformer") goes to the window
+    kernel; anything narrower, wider, denser, shorter or in half precision does not."""
+    def chosen(m, k, n, nnz, eb=4):
+        return spdl.spdl_variant_name(0, spdl.spdl_select_spmm(m, k, n, nnz, eb, 0, 0)["variant"])
+    assert chosen(4096, 4096, 64, 1678008) == "window"            # config 4
+    assert chosen(12288, 12288, 64, 12288 * 800) == "window"      # the paper's own sequence length
+    assert chosen(4096, 4096, 32, 1678008) == "rowsplit"
+    assert chosen(4096, 4096, 128, 1678008) != "window"
+    assert chosen(2048, 2048, 64, 2048 * 400) == "rowsplit"
+    assert chosen(4096, 4096, 64, 4096 * 100) == "rowsplit"       # short rows
+    assert chosen(8192, 8192, 64, int(8192 * 8192 * 0.3)) == "slabdma"
+    assert chosen(4096, 4096, 64, 1678008, eb=2) != "window"
+    try:
+        spdl.spdl_force_variant(0, 4)
+        assert chosen(4096, 4096, 64, 0) == "rowsplit"            # nothing to fetch from
+        assert chosen(64, 64, 130, 100) == "rowsplit"             # n % 4 != 0
+        assert chosen(203, 700, 1028, 3000) == "window"
+    finally:
+        spdl.spdl_force_variant(0, -1)
+
+
+def test_sddmm_selection_of_the_window_kernel(spdl):
+    def chosen(m, k, n, nnz, eb=4):
+        return spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(m, k, n, nnz, eb, 0, 0)["variant"])
+    assert chosen(4096, 4096, 64, 1678008) == "window"            # config 4
+    assert chosen(4096, 4096, 32, 1678008) == "group"
+    assert chosen(4096, 4096, 128, 1678008) == "lane"
+    assert chosen(2048, 8192, 64, 2048 * 400) == "group"           # too few rows
+    assert chosen(4096, 4096, 64, 4096 * 100) == "group"          # short rows
+    assert chosen(4096, 4096, 64, 1678008, eb=2) != "window"
+    try:
+        spdl.spdl_force_variant(1, 6)
+        assert chosen(203, 700, 64, 3000) == "window"
+        assert chosen(203, 700, 68, 3000) == "group"              # dot products of at most 64 columns
+    finally:
+        spdl.spdl_force_variant(1, -1)
+
+
 def test_forced_slab_variants_never_run_an_empty_matrix(spdl):
     """With nnz == 0 the sparse arrays and B may be null; the kernels that fetch from them
     unconditionally must not be chosen, forced or not."""
     try:
-        for forced in (1, 2, 3):
+        for forced in (1, 2, 3, 4):
             spdl.spdl_force_variant(0, forced)
             for eb in (4, 2):
                 s = spdl.spdl_select_spmm(4096, 4096, 128, 0, eb, 0, 0)
