@@ -57,8 +57,10 @@ typedef enum {
  *               The result does not depend on it.
  *   B : DEVICE fp32[k*n];   C : DEVICE fp32[m*n], fully overwritten (empty rows become +0).
  *   Products and sums are fp32 (fused multiply-adds).  Most kernels add a row's products in
- *   stored order; when few long rows are spread over several lane groups, partial sums are added
- *   at the end.  Either way the result is deterministic and does not depend on row_order. */
+ *   stored order; when few long rows are spread over several lane groups, and in the kernel for
+ *   attention-shaped problems (33..64 columns, which keeps a window of B around a band of A in
+ *   on-chip memory and takes rows in their natural order), partial sums are added at the end.
+ *   Either way the result is deterministic and does not depend on row_order. */
 int spdl_spmm(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
               const float* values, const int* row_order, const float* B, float* C, void* stream);
 
