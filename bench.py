@@ -213,6 +213,22 @@ def extra_cases(groups, wl, spdl, torch):
         w = wl.attention(0)
         extra.append(Case("attention_head", "sddmm", w["A"], 64, (w["Q"], w["K"]), spdl, torch))
         extra.append(Case("attention_head", "spmm", w["A"], 64, (w["V"],), spdl, torch))
+        # The same mask with heads of 128 columns (hidden 1024 over 8 heads, paper Sec. "Application:
+        # Sparse Transformer"): what spdl_spmm / spdl_sddmm choose from the shape alone, and the entry
+        # points for banded masks, which the caller of an attention layer can name.
+        A = w["A"]
+        Q2, K2, V2 = wl.dense(A.m, 128, 611), wl.dense(A.k, 128, 612), wl.dense(A.k, 128, 613)
+        extra.append(Case("attention_head_n128", "sddmm", A, 128, (Q2, K2), spdl, torch))
+        extra.append(Case("attention_head_n128", "spmm", A, 128, (V2,), spdl, torch))
+        ro, ci, val = dev(A.row_offsets), dev(A.column_indices), dev(A.values)
+        dQ, dK, dV = dev(Q2), dev(K2), dev(V2)
+        out2, C2 = torch.empty(A.nnz, device="cuda"), torch.empty((A.m, 128), device="cuda")
+        extra.append(WidenedCase("attention_head_n128", "sddmm_banded", "window", A.nnz,
+                                 lambda: spdl.spdl_sddmm_banded(A.m, A.k, 128, A.nnz, ro, ci, dQ, dK, out2),
+                                 sddmm_bytes(A.m, A.k, 128, A.nnz), 2.0 * A.nnz * 128, dims=(A.m, A.k, 128)))
+        extra.append(WidenedCase("attention_head_n128", "spmm_banded", "window", A.nnz,
+                                 lambda: spdl.spdl_spmm_banded(A.m, A.k, 128, A.nnz, ro, ci, val, dV, C2),
+                                 spmm_bytes(A.m, A.k, 128, A.nnz), 2.0 * A.nnz * 128, dims=(A.m, A.k, 128)))
     if "conv_f16" in groups:                # sparse 1x1 convolution, fp16 in / fp32 accumulate
         for skew in (False, True):
             w = wl.conv1x1(skew)

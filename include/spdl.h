@@ -73,6 +73,23 @@ int spdl_spmm(int m, int k, int n, int nnz, const int* row_offsets, const int* c
 int spdl_sddmm(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                const float* L, const float* R, float* out_values, void* stream);
 
+/* SpMM and SDDMM for a sparse matrix whose entries cluster around a band: the attention masks of
+ * paper Sec. "Application: Sparse Transformer" (a dense band along the diagonal plus scattered
+ * entries).  Same operations, arguments and results as spdl_spmm (without a row order: rows are
+ * taken in their natural order, neighbours share the band) and spdl_sddmm; the only difference is
+ * the choice of kernel, which the library cannot make by itself because it never reads the
+ * topology on the host: a window of the dense operand around the band is kept in on-chip memory
+ * and only the scattered entries are gathered.  Where the band is, and whether there is one, is
+ * found on the device; without a band every entry is gathered and the result is still right.
+ * Used as given for fp32 with n % 4 == 0, 16-byte aligned dense operands and k*n < 2^29 (SDDMM:
+ * n <= 128); any other problem runs exactly as through spdl_spmm / spdl_sddmm.  spdl_spmm and
+ * spdl_sddmm themselves pick these kernels for 33..64 columns, 4096 rows or more, 192 entries
+ * per row or more and at most 1/8 density. */
+int spdl_spmm_banded(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                     const float* values, const float* B, float* C, void* stream);
+int spdl_sddmm_banded(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                      const float* L, const float* R, float* out_values, void* stream);
+
 /* SDDMM with the row order of SpMM (paper Sec. "Row Swizzle Load Balancing"; the paper applies the
  * swizzle to SpMM, the kernels here that give a sparse row to one lane group profit in the same way):
  *   row_order : DEVICE int32[m], a permutation of [0,m) (spdl_build_row_order), or NULL.

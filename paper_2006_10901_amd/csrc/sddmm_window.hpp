@@ -1,6 +1,6 @@
 // SDDMM, window family: the counterpart of the window SpMM kernel for sparse matrices whose
 // entries cluster around a band (the attention masks of paper Sec. "Application: Sparse
-// Transformer") and dot products of at most 64 columns (one attention head).  A workgroup owns
+// Transformer") and dot products of at most 128 columns (one attention head).  A workgroup owns
 // NW consecutive sparse rows, one per wave, and copies ONE window of 256 consecutive rows of R
 // into LDS, placed where its rows have most of their entries.  A row is cut into strips of 16
 // consecutive entries, dealt to the wave's four 16-lane groups; a strip whose 16 columns all lie
@@ -9,7 +9,8 @@
 // (four columns of the dot product per lane, one partial sum per entry, a transposing reduction
 // that leaves entry t's result in lane t), so both give the same bits.
 // Any CSR input gives the right result; the window's position is only a matter of speed.
-// Needs n <= 64, n % 4 == 0, 16-byte aligned L and R, k * n < 2^29.
+// NC = chunks of 64 columns of the dot product (1 or 2); the window holds 256 rows x 64 NC columns
+// of R, chunk after chunk.  Needs n <= 64 NC, n % 4 == 0, 16-byte aligned L and R, k * n < 2^29.
 #pragma once
 #include "common.hpp"
 #include "sddmm_group.hpp"
@@ -17,12 +18,13 @@
 
 namespace spdl {
 
-template <int NW>
+template <int NW, int NC>
 __global__ __launch_bounds__(64 * NW) void sddmm_window_kernel(
     int m, int k, int n, int nnz, const int* __restrict__ row_offsets,
     const int* __restrict__ column_indices, const float* __restrict__ L, const float* __restrict__ R,
     float* __restrict__ out, const float* __restrict__ scale) {
   constexpr int W = 256;
+  constexpr int kChunkBytes = W * 64 * 4;           // one 64-column chunk of the window
   constexpr int kCopies = W / (4 * NW);
   static_assert(W % (4 * NW) == 0, "every wave copies the same number of 4-row pieces");
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
@@ -32,28 +34,36 @@ __global__ __launch_bounds__(64 * NW) void sddmm_window_kernel(
   const int wave = uniform(tid >> 6);
   const int sub = lane >> 4;
   const int l16 = lane & 15;
-  const int col = l16 * 4;
-  const bool col_ok = col < n;
-  const int lane_b = col_ok ? l16 * 16 : 0;
+  // this lane's four columns of chunk c: 64 c + 4 l16 .. + 3 (past n: the chunk's first four, times zero)
+  bool col_ok[NC];
+  int lane_b[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    col_ok[c] = 64 * c + l16 * 4 < n;
+    lane_b[c] = col_ok[c] ? l16 * 16 : 0;
+  }
 
   const int r0 = blockIdx.x * NW;
   const int r1 = min(m, r0 + NW) - 1;
   const int c0 = win_place<W>(row_offsets, column_indices, r0, r1, k);
 
-  // The window copy: copy i of wave w fills window rows (i*NW + w)*4 .. +3 (256 bytes each in
-  // LDS), lane L row L/16 of those and columns 4*(L%16) .. +3; rows past k are clamped to row
-  // k-1 and columns past n to column 0 (nothing valid reads those).
+  // The window copy, chunk after chunk: copy i of wave w fills window rows (i*NW + w)*4 .. +3 (256
+  // bytes each in LDS), lane L row L/16 of those and columns 4*(L%16) .. +3 of the chunk; rows past
+  // k are clamped to row k-1 and columns past n to the chunk's first (nothing valid reads those).
   if (c0 < k) {
-    const char* base = reinterpret_cast<const char*>(R);
     const unsigned dst = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds_raw +
                          (unsigned)wave * (4 * 64 * 4);
 #pragma unroll
-    for (int i = 0; i < kCopies; ++i) {
-      const int lrow = (i * NW + wave) * 4 + sub;
-      const unsigned voff = (unsigned)min(c0 + lrow, k - 1) * (unsigned)n * 4u + (unsigned)lane_b;
-      const unsigned m0v = dst + (unsigned)i * (NW * 4 * 64 * 4);
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                   :: "s"(m0v), "v"(voff), "s"(base) : "memory", "m0");
+    for (int c = 0; c < NC; ++c) {
+      const char* base = reinterpret_cast<const char*>(R + 64 * c);
+#pragma unroll
+      for (int i = 0; i < kCopies; ++i) {
+        const int lrow = (i * NW + wave) * 4 + sub;
+        const unsigned voff = (unsigned)min(c0 + lrow, k - 1) * (unsigned)n * 4u + (unsigned)lane_b[c];
+        const unsigned m0v = dst + (unsigned)(c * kChunkBytes + i * (NW * 4 * 64 * 4));
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :: "s"(m0v), "v"(voff), "s"(base) : "memory", "m0");
+      }
     }
   }
 
@@ -62,10 +72,13 @@ __global__ __launch_bounds__(64 * NW) void sddmm_window_kernel(
   const int p_begin = row_ok ? row_offsets[row] : 0;
   const int p_end = row_ok ? row_offsets[row + 1] : 0;
   const float* Lrow = L + (size_t)(row_ok ? row : 0) * n;
-  float l[4];
-  Pack<float, 4>::load(Lrow + (col_ok ? col : 0), l);
+  float l[NC][4];
 #pragma unroll
-  for (int v = 0; v < 4; ++v) l[v] = col_ok ? l[v] : 0.f;
+  for (int c = 0; c < NC; ++c) {
+    Pack<float, 4>::load(Lrow + 64 * c + (col_ok[c] ? l16 * 4 : 0), l[c]);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) l[c][v] = col_ok[c] ? l[c][v] : 0.f;
+  }
 
   // the column of this lane's entry of the strip at `at`; past the row end the last entry's again
   auto fetch = [&](int at) { return column_indices[max(min(at + l16, p_end - 1), 0)]; };
@@ -83,20 +96,25 @@ __global__ __launch_bounds__(64 * NW) void sddmm_window_kernel(
     if (at < p_end) {
       if (group_in) {
         const int off = (int)(rel * 256u);
-        f32x4 r[16];
-#define SPDL_W1(T0) \
-        r[T0] = *reinterpret_cast<const f32x4*>(lds_raw + (__builtin_amdgcn_update_dpp(0, off, 0x150 + (T0), 0xf, 0xf, false) + lane_b));
-        SPDL_W1(0) SPDL_W1(1) SPDL_W1(2) SPDL_W1(3) SPDL_W1(4) SPDL_W1(5) SPDL_W1(6) SPDL_W1(7)
-        SPDL_W1(8) SPDL_W1(9) SPDL_W1(10) SPDL_W1(11) SPDL_W1(12) SPDL_W1(13) SPDL_W1(14) SPDL_W1(15)
-#undef SPDL_W1
         float partial[16];
 #pragma unroll
-        for (int t = 0; t < 16; ++t) {
-          partial[t] = 0.f;
-          partial[t] = __builtin_fmaf(l[0], r[t].x, partial[t]);
-          partial[t] = __builtin_fmaf(l[1], r[t].y, partial[t]);
-          partial[t] = __builtin_fmaf(l[2], r[t].z, partial[t]);
-          partial[t] = __builtin_fmaf(l[3], r[t].w, partial[t]);
+        for (int t = 0; t < 16; ++t) partial[t] = 0.f;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+          f32x4 r[16];
+          const char* chunk = lds_raw + c * kChunkBytes + lane_b[c];
+#define SPDL_W1(T0) \
+          r[T0] = *reinterpret_cast<const f32x4*>(chunk + __builtin_amdgcn_update_dpp(0, off, 0x150 + (T0), 0xf, 0xf, false));
+          SPDL_W1(0) SPDL_W1(1) SPDL_W1(2) SPDL_W1(3) SPDL_W1(4) SPDL_W1(5) SPDL_W1(6) SPDL_W1(7)
+          SPDL_W1(8) SPDL_W1(9) SPDL_W1(10) SPDL_W1(11) SPDL_W1(12) SPDL_W1(13) SPDL_W1(14) SPDL_W1(15)
+#undef SPDL_W1
+#pragma unroll
+          for (int t = 0; t < 16; ++t) {
+            partial[t] = __builtin_fmaf(l[c][0], r[t].x, partial[t]);
+            partial[t] = __builtin_fmaf(l[c][1], r[t].y, partial[t]);
+            partial[t] = __builtin_fmaf(l[c][2], r[t].z, partial[t]);
+            partial[t] = __builtin_fmaf(l[c][3], r[t].w, partial[t]);
+          }
         }
         const float total = reduce16x16(partial, l16);
         if (at + l16 < p_end) sddmm_store<float>(out, scale, at + l16, total);

@@ -179,7 +179,8 @@ bool spmm_mfma_runnable() {
 }
 
 template <typename T>
-void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, spdl_launch_info* info) {
+void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, spdl_launch_info* info,
+                    bool banded = false) {
   int variant = g_forced[0].load();
   const bool mfma_ok = sizeof(T) == 2 && n % 8 == 0 && n < (1 << 24) && k >= 16 && aligned(B, 16) && aligned(C, 16);
   // nnz == 0: column_indices, values and B may be null, and the slab and matrix-core kernels
@@ -220,6 +221,8 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
     if (sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) && (int64_t)k * n < ((int64_t)1 << 29) && n > 32 &&
         n <= kWinTile && m >= 4096 && (double)nnz >= 192.0 * (double)m && (double)nnz <= 0.125 * (double)m * (double)k)
       variant = kSpmmWindow;
+    // the caller says that the entries form a band
+    if (banded) variant = kSpmmWindow;
   }
   if (variant == kSpmmWindow && sizeof(T) == 4 && nnz > 0 && slab_usable<T>(n, nnz, B, C) &&
       (int64_t)k * n < ((int64_t)1 << 29)) {
@@ -283,13 +286,14 @@ int launch_spmm_rowsplit(const spdl_launch_info& li, int m, int n, const int* ro
 
 template <typename T, typename I = int>
 int spmm_impl(int m, int k, int n, int nnz, const int* ro, const I* ci, const T* val,
-              const int* order, const T* B, T* C, void* stream, const T* bias = nullptr, int relu = 0) {
+              const int* order, const T* B, T* C, void* stream, const T* bias = nullptr, int relu = 0,
+              bool banded = false) {
   if (!sizes_ok(m, k, n, nnz)) return SPDL_ERR_INVALID;
   if (m == 0 || n == 0) return SPDL_OK;
   if (!ro || !C || (nnz > 0 && (!ci || !val || !B))) return SPDL_ERR_INVALID;
   hipStream_t st = static_cast<hipStream_t>(stream);
   spdl_launch_info li;
-  fill_spmm_info<T>(m, k, n, nnz, B, C, &li);
+  fill_spmm_info<T>(m, k, n, nnz, B, C, &li, banded);
   (void)hipGetLastError();
   int rc = SPDL_OK;
   constexpr bool kInt32 = sizeof(I) == 4;        // the slab kernels read 32-bit indices only
@@ -448,9 +452,11 @@ bool sddmm_lane_usable(int n, int nnz, const void* L, const void* R) {
 }
 
 template <typename T>
-void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R, spdl_launch_info* info) {
+void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R, spdl_launch_info* info,
+                     bool banded = false) {
   const bool fast_ok = sddmm_group_usable<T>(n, L, R);
   int variant = g_forced[1].load();
+  const bool free_choice = variant < 0;
   const bool mfma_ok = sizeof(T) == 2 && n > 0 && n % 8 == 0 && aligned(L, 16) && aligned(R, 16) &&
                        (int64_t)((m + 63) / 64) * ((k + 63) / 64) < ((int64_t)1 << 31);
   if (variant == kSddmmMfma && !mfma_ok) variant = kSddmmGroup;
@@ -522,7 +528,8 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
       !(fast_ok && sizeof(T) == 4 && nnz < (1 << 29) && n < (1 << 21)))   // 32-bit byte offsets
     variant = kSddmmGroup;
   if (variant == kSddmmLane && !sddmm_lane_usable<T>(n, nnz, L, R)) variant = kSddmmGroup;
-  if (variant == kSddmmWindow && !(sizeof(T) == 4 && fast_ok && aligned(L, 16) && aligned(R, 16) && n <= kWinTile &&
+  if (free_choice && banded) variant = kSddmmWindow;          // the caller says that the entries form a band
+  if (variant == kSddmmWindow && !(sizeof(T) == 4 && fast_ok && aligned(L, 16) && aligned(R, 16) && n <= 2 * kWinTile &&
                                    nnz > 0 && (int64_t)k * n < ((int64_t)1 << 29)))
     variant = kSddmmGroup;
   if (variant == kSddmmGroup && !fast_ok) variant = kSddmmRowstrip;
@@ -612,13 +619,13 @@ int launch_sddmm_slab(const SddmmSlabShape& sh, int grid, int m, int k, int n, i
 
 template <typename T>
 int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const T* L, const T* R,
-               T* out, void* stream, const T* scale = nullptr, const int* order = nullptr) {
+               T* out, void* stream, const T* scale = nullptr, const int* order = nullptr, bool banded = false) {
   if (!sizes_ok(m, k, n, nnz)) return SPDL_ERR_INVALID;
   if (m == 0 || nnz == 0) return SPDL_OK;
   if (!ro || !ci || !out || (n > 0 && (!L || !R))) return SPDL_ERR_INVALID;
   hipStream_t st = static_cast<hipStream_t>(stream);
   spdl_launch_info li;
-  fill_sddmm_info<T>(m, k, n, nnz, L, R, &li);
+  fill_sddmm_info<T>(m, k, n, nnz, L, R, &li, banded);
   dim3 grid(li.grid_x), block(256);
   const int split = li.rows_per_block;
   (void)hipGetLastError();
@@ -681,15 +688,21 @@ int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const
   if (li.variant == kSddmmWindow) {
     if constexpr (sizeof(T) == 4) {
       static std::atomic<bool> configured{false};
-      auto kernel = sddmm_window_kernel<kWinWaves>;
-      constexpr int lds = 256 * 64 * 4;
+      constexpr int lds1 = 256 * 64 * 4;
       if (!configured.load()) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
-            hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(sddmm_window_kernel<kWinWaves, 1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds1) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(sddmm_window_kernel<kWinWaves, 2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * lds1) != hipSuccess)
           return SPDL_ERR_LAUNCH;
         configured.store(true);
       }
-      kernel<<<dim3(li.grid_x), dim3(li.block_threads), lds, st>>>(m, k, n, nnz, ro, ci, L, R, out, scale);
+      if (n <= kWinTile)
+        sddmm_window_kernel<kWinWaves, 1><<<dim3(li.grid_x), dim3(li.block_threads), lds1, st>>>(m, k, n, nnz, ro, ci, L,
+                                                                                                 R, out, scale);
+      else
+        sddmm_window_kernel<kWinWaves, 2><<<dim3(li.grid_x), dim3(li.block_threads), 2 * lds1, st>>>(m, k, n, nnz, ro, ci,
+                                                                                                     L, R, out, scale);
       return hipGetLastError() == hipSuccess ? SPDL_OK : SPDL_ERR_LAUNCH;
     } else {
       return SPDL_ERR_UNSUPPORTED;
@@ -834,6 +847,16 @@ int spdl_permute_values(int nnz, int elem_bytes, const int* perm, const void* va
 int spdl_sddmm(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                const float* L, const float* R, float* out_values, void* stream) {
   return sddmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stream);
+}
+
+int spdl_spmm_banded(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                     const float* values, const float* B, float* C, void* stream) {
+  return spmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, values, nullptr, B, C, stream, nullptr, 0, true);
+}
+
+int spdl_sddmm_banded(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                      const float* L, const float* R, float* out_values, void* stream) {
+  return sddmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stream, nullptr, nullptr, true);
 }
 
 int spdl_sddmm_ordered(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,

@@ -356,9 +356,9 @@ def test_forced_sddmm_variants_ragged(g, oracle_lib, force, n):
             force(1, v)
             chosen = spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"])
             # (the lane kernel takes dot products of more than 128 columns in passes of 128; the window
-            # kernel is for dot products of at most 64 columns)
+            # kernel is for dot products of at most 128 columns)
             name = spdl.spdl_variant_name(1, v)
-            assert chosen == ("group" if name == "window" and n > 64 else name)
+            assert chosen == ("group" if name == "window" and n > 128 else name)
             got = g.gpu_sddmm(A, L, R, n)
             g.assert_close(got, out, S, g.TOL_F32, f"sddmm variant {spdl.spdl_variant_name(1, v)} n={n}")
 
@@ -403,7 +403,7 @@ def test_forced_sddmm_variants_fp16_and_long_rows(g, oracle_lib, force):
             g.assert_close(got, out, S, tol, f"sddmm variant {spdl.spdl_variant_name(1, v)} {dt.__name__}")
 
 
-@pytest.mark.parametrize("n", [36, 64])
+@pytest.mark.parametrize("n", [36, 64, 100, 128])
 def test_window_kernels_on_banded_masks(g, oracle_lib, force, n):
     """The window kernels (one window of 256 rows of the dense operand in LDS per 16 sparse rows,
     gathers for the rest) on masks with a band: a row count that is not a multiple of 16, fewer
@@ -431,6 +431,16 @@ def test_window_kernels_on_banded_masks(g, oracle_lib, force, n):
         assert np.array_equal(got, g.gpu_sddmm(A, L, B, n))
         force(0, -1)
         force(1, -1)
+        # the entry points for banded masks choose the same kernels by themselves: same bits
+        import torch
+        d = g.DevCsr(A)
+        Cb = torch.full((A.m, n), float("nan"), device="cuda")
+        ob = torch.full((A.nnz,), float("nan"), device="cuda")
+        spdl.spdl_spmm_banded(A.m, A.k, n, A.nnz, d.ro, d.ci, d.val, g.dev(B), Cb)
+        spdl.spdl_sddmm_banded(A.m, A.k, n, A.nnz, d.ro, d.ci, g.dev(L), g.dev(B), ob)
+        torch.cuda.synchronize()
+        g.assert_close(Cb.cpu().numpy(), C, S, g.TOL_F32, f"spmm_banded case {idx} n={n}")
+        assert np.array_equal(ob.cpu().numpy(), got)
 
 
 # ------------------------------------------------------------------ matrix-core kernels (fp16)

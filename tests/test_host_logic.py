@@ -206,7 +206,8 @@ def test_sddmm_selection_of_the_window_kernel(spdl):
     try:
         spdl.spdl_force_variant(1, 6)
         assert chosen(203, 700, 64, 3000) == "window"
-        assert chosen(203, 700, 68, 3000) == "group"              # dot products of at most 64 columns
+        assert chosen(203, 700, 68, 3000) == "window"
+        assert chosen(203, 700, 132, 3000) == "group"             # dot products of at most 128 columns
     finally:
         spdl.spdl_force_variant(1, -1)
 
