@@ -51,6 +51,10 @@ def test_invalid_arguments_are_rejected_without_a_gpu(spdl):
     assert lib.spdl_sddmm(4, 4, 4, 3, one, one, null, one, one, null) == -1
     assert lib.spdl_spmm_f16(4, -4, 4, 3, one, one, one, null, one, one, null) == -1
     assert lib.spdl_sddmm_f16(4, 4, 4, 3, one, one, one, one, null, null) == -1
+    assert lib.spdl_spmm_banded(4, 4, 4, 3, one, null, one, one, one, null) == -1
+    assert lib.spdl_sddmm_banded(4, 4, -4, 3, one, one, one, one, one, null) == -1
+    assert lib.spdl_spmm_banded(0, 4, 4, 0, null, null, null, null, null, null) == 0
+    assert lib.spdl_sddmm_banded(4, 4, 4, 0, one, null, one, one, null, null) == 0
     # degenerate sizes succeed without launching anything
     assert lib.spdl_spmm(0, 4, 4, 0, null, null, null, null, null, null, null) == 0
     assert lib.spdl_spmm(4, 4, 0, 0, one, null, null, null, null, null, null) == 0
