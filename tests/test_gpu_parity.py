@@ -407,15 +407,15 @@ def test_forced_sddmm_variants_fp16_and_long_rows(g, oracle_lib, force):
 def test_window_kernels_on_banded_masks(g, oracle_lib, force, n):
     """The window kernels (one window of 256 rows of the dense operand in LDS per 16 sparse rows,
     gathers for the rest) on masks with a band: a row count that is not a multiple of 16, fewer
-    columns than a window holds, a band that is not on the diagonal of a rectangular matrix, and a
-    uniform mask, for which no window is placed.  SDDMM gives the bits of the nonzero-split kernel."""
+    columns than a window holds, a band that is not on the diagonal of a rectangular matrix, a
+    uniform mask, for which no window is placed, and a causal mask (band to the left of the diagonal).  SDDMM gives the bits of the nonzero-split kernel."""
     import paper_2006_10901_amd as spdl
     v0 = {spdl.spdl_variant_name(0, v): v for v in spmm_variants()}
     v1 = {spdl.spdl_variant_name(1, v): v for v in sddmm_variants()}
     shifted = wl.banded_attention_csr(600, 128, 0.3, 2105 + n)
     shifted = wl.Csr(600, 1500, shifted.row_offsets, (shifted.column_indices + 700).astype(np.int32), shifted.values)
     cases = [wl.banded_attention_csr(1000, 128, 0.2, 2100 + n), wl.banded_attention_csr(200, 64, 0.5, 2101 + n),
-             shifted, wl.uniform_mask_csr(500, 3000, 0.1, 2102 + n)]
+             shifted, wl.uniform_mask_csr(500, 3000, 0.1, 2102 + n), wl.causal_attention_csr(900, 256, 0.05, 2106 + n)]
     for idx, A in enumerate(cases):
         B, L = wl.dense(A.k, n, 2103 + n), wl.dense(A.m, n, 2104 + n)
         C, S = oracle_lib.spmm(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, B)

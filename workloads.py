@@ -131,6 +131,25 @@ def banded_attention_csr(seq, band, density, seed, sigma=1.0) -> Csr:
     return Csr(seq, seq, ro.astype(np.int32), cc.astype(np.int32), vals)
 
 
+def causal_attention_csr(seq, band, off_density, seed, sigma=1.0) -> Csr:
+    """Causal mask: the band i - band < j <= i, plus entries to the left of it kept with probability
+    proportional to 1/(i - j), scaled so that `off_density` of those positions are kept (the mask of
+    paper Sec. "Application: Sparse Transformer": band 256, 5 % off the band, sequence 12,288)."""
+    rng = np.random.default_rng(seed)
+    i = np.arange(seq)[:, None]
+    j = np.arange(seq)[None, :]
+    d = i - j
+    left = d >= band
+    w = np.where(left, 1.0 / np.maximum(d, 1), 0.0)
+    p = np.minimum(1.0, w * (off_density * left.sum() / max(w.sum(), 1e-30)))
+    keep = ((d >= 0) & (d < band)) | (rng.random((seq, seq)) < p)
+    rr, cc = np.nonzero(keep)
+    ro = np.zeros(seq + 1, dtype=np.int64)
+    np.cumsum(np.bincount(rr, minlength=seq), out=ro[1:])
+    vals = rng.standard_normal(int(ro[-1]), dtype=np.float32) * np.float32(sigma)
+    return Csr(seq, seq, ro.astype(np.int32), cc.astype(np.int32), vals)
+
+
 def dense(rows, cols, seed, dtype=np.float32) -> np.ndarray:
     rng = np.random.default_rng(seed)
     x = rng.standard_normal((rows, cols), dtype=np.float32)
