@@ -208,18 +208,26 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
     // one workgroup per CU: below half a machine of 64x64 output tiles the row-splitting
     // kernel, which spreads over many more waves, is faster
     const int64_t out_tiles = (int64_t)((m + kSlabRows - 1) / kSlabRows) * ((n + kSlabTile - 1) / kSlabTile);
-    variant = (sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) && reuse >= 2.0 && out_tiles >= kComputeUnits / 2)
+    // (Narrow outputs: a row of B is one or two cache lines, which makes gathering cheap, and outputs
+    // of at most 32 columns use half of a slab tile's lanes or less.  8192 x 8192 at 5 % density:
+    // slab 58 us against 26 for gathers at n = 32, 56 against 45 at n = 64; at 10 % the slab kernel
+    // wins at n = 64, 66 us against 82, and still loses at n = 32, 68 against 46.)
+    const double min_reuse = n <= 32 ? 12.0 : n <= 64 ? 5.0 : 2.0;
+    variant = (sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) && reuse >= min_reuse && out_tiles >= kComputeUnits / 2)
                   ? kSpmmSlabDma : kSpmmRowsplit;
-    // One 64-column tile, rows of a few hundred entries, at most 1/8 dense: the shape of an
-    // attention head (paper Sec. "Application: Sparse Transformer").  The host cannot see whether
-    // the entries form a band; the window kernel is chosen because it is the fastest of the three
-    // when they do (sequence 4096 .. 12288, band 256: 1.2 .. 1.3 times the row-splitting kernel
-    // and 2.2 .. 2.6 times the slab kernel, which walks every slab of B for a handful of entries)
-    // and within 15 % of the best when they do not (its gathers are the row-splitting kernel's).
-    // Narrower outputs leave its lanes idle, fewer rows leave it too few waves, and denser or
-    // wider problems without a band belong to the slab kernel.
-    if (sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) && (int64_t)k * n < ((int64_t)1 << 29) && n > 32 &&
-        n <= kWinTile && m >= 4096 && (double)nnz >= 192.0 * (double)m && (double)nnz <= 0.125 * (double)m * (double)k)
+    // One 64-column tile, thousands of rows of a few hundred entries, at most 1/8 dense, and not
+    // enough output tiles for the slab kernel: the shape of an attention head (paper Sec.
+    // "Application: Sparse Transformer").  The host cannot see whether the entries form a band;
+    // where the choice is between gathering and the window kernel the latter loses nothing without
+    // a band (its gathers are the row-splitting kernel's: 40.7 us against 44.6 on a uniform
+    // 8192 x 8192 mask at 5 %) and is 1.2 .. 1.3 times faster with one.  Narrower outputs leave its
+    // lanes idle and fewer rows leave it too few waves.  Where the slab kernel applies it stays the
+    // choice from the shape alone: on uniform masks it is up to 1.9 times faster than the window
+    // kernel (16384 x 4096 at 10 %), on banded ones 2.2 .. 2.6 times slower, and only the caller
+    // knows which it is (spdl_spmm_banded).
+    if (variant == kSpmmRowsplit && sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) &&
+        (int64_t)k * n < ((int64_t)1 << 29) && n > 32 && n <= kWinTile && m >= 4096 &&
+        (double)nnz >= 192.0 * (double)m && (double)nnz <= 0.125 * (double)m * (double)k)
       variant = kSpmmWindow;
     // the caller says that the entries form a band
     if (banded) variant = kSpmmWindow;

@@ -182,7 +182,13 @@ def test_spmm_selection_of_the_window_kernel(spdl):
     def chosen(m, k, n, nnz, eb=4):
         return spdl.spdl_variant_name(0, spdl.spdl_select_spmm(m, k, n, nnz, eb, 0, 0)["variant"])
     assert chosen(4096, 4096, 64, 1678008) == "window"            # config 4
-    assert chosen(12288, 12288, 64, 12288 * 800) == "window"      # the paper's own sequence length
+    assert chosen(12288, 12288, 64, 12288 * 800) == "window"      # the paper's own sequence length, 6.5 % dense
+    # dense enough for slabs of 64 columns: the shape alone keeps them (spdl_spmm_banded is for the caller who knows)
+    assert chosen(12288, 12288, 64, int(12288 * 12288 * 0.1)) == "slabdma"
+    assert chosen(8192, 8192, 64, int(8192 * 8192 * 0.1)) == "slabdma"
+    assert chosen(8192, 8192, 64, int(8192 * 8192 * 0.05)) == "window"        # too sparse for slabs of 64 columns
+    assert chosen(8192, 8192, 32, int(8192 * 8192 * 0.05)) == "rowsplit"     # narrow output: gathers
+    assert chosen(8192, 8192, 32, int(8192 * 8192 * 0.3)) == "slabdma"
     assert chosen(4096, 4096, 32, 1678008) == "rowsplit"
     assert chosen(4096, 4096, 128, 1678008) != "window"
     assert chosen(2048, 2048, 64, 2048 * 400) == "rowsplit"
