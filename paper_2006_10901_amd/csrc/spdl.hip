@@ -494,7 +494,11 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
       // columns: the lane kernel, as long as a panel of 64 rows meets the same row of R at least
       // once on average.
       const bool lane = fp32_fast && n > 64 && reuse >= 1.0;
-      const bool slab = fp32_fast && reuse >= 2.0 && (n >= 128 || reuse >= 8.0);
+      // (5 <= reuse < 8 with at least 128 panels of 64 rows: on uniform masks the slab kernel is then
+      // 1.25 .. 1.4 times faster than gathering, 8192 x 2048 at 10 %: 18.7 us against 25; with 64
+      // panels it has to split A's columns over workgroups and the banded attention mask of 4096
+      // rows, also 10 % dense, takes 36 us against 24)
+      const bool slab = fp32_fast && reuse >= 2.0 && (n >= 128 || reuse >= 8.0 || (reuse >= 5.0 && m >= 8192));
       variant = lane ? kSddmmLane : slab ? kSddmmSlabDma : kSddmmGroup;
       // The shape of an attention head (33..64 columns, thousands of rows of a few hundred entries,
       // at most 1/8 dense; paper Sec. "Application: Sparse Transformer"): the window kernel, which is

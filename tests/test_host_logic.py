@@ -213,6 +213,10 @@ def test_sddmm_selection_of_the_window_kernel(spdl):
     assert chosen(2048, 8192, 64, 2048 * 400) == "group"           # too few rows
     assert chosen(4096, 4096, 64, 4096 * 100) == "group"          # short rows
     assert chosen(4096, 4096, 64, 1678008, eb=2) != "window"
+    # uniform masks of that density with enough rows for full slab panels: the slab kernel
+    assert chosen(8192, 2048, 64, int(8192 * 2048 * 0.1)) == "slabdma"
+    assert chosen(16384, 4096, 32, int(16384 * 4096 * 0.1)) == "slabdma"
+    assert chosen(8192, 8192, 64, int(8192 * 8192 * 0.05)) == "window"
     try:
         spdl.spdl_force_variant(1, 6)
         assert chosen(203, 700, 64, 3000) == "window"
