@@ -229,8 +229,10 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
         (int64_t)k * n < ((int64_t)1 << 29) && n > 32 && n <= kWinTile && m >= 4096 &&
         (double)nnz >= 192.0 * (double)m && (double)nnz <= 0.125 * (double)m * (double)k)
       variant = kSpmmWindow;
-    // the caller says that the entries form a band
-    if (banded) variant = kSpmmWindow;
+    // the caller says that the entries form a band (a problem the window kernel cannot take keeps
+    // the choice made above)
+    if (banded && sizeof(T) == 4 && nnz > 0 && slab_usable<T>(n, nnz, B, C) && (int64_t)k * n < ((int64_t)1 << 29))
+      variant = kSpmmWindow;
   }
   if (variant == kSpmmWindow && sizeof(T) == 4 && nnz > 0 && slab_usable<T>(n, nnz, B, C) &&
       (int64_t)k * n < ((int64_t)1 << 29)) {
@@ -540,10 +542,12 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
       !(fast_ok && sizeof(T) == 4 && nnz < (1 << 29) && n < (1 << 21)))   // 32-bit byte offsets
     variant = kSddmmGroup;
   if (variant == kSddmmLane && !sddmm_lane_usable<T>(n, nnz, L, R)) variant = kSddmmGroup;
-  if (free_choice && banded) variant = kSddmmWindow;          // the caller says that the entries form a band
-  if (variant == kSddmmWindow && !(sizeof(T) == 4 && fast_ok && aligned(L, 16) && aligned(R, 16) && n <= 2 * kWinTile &&
-                                   nnz > 0 && (int64_t)k * n < ((int64_t)1 << 29)))
-    variant = kSddmmGroup;
+  const bool window_ok = sizeof(T) == 4 && fast_ok && aligned(L, 16) && aligned(R, 16) && n <= 2 * kWinTile && nnz > 0 &&
+                         (int64_t)k * n < ((int64_t)1 << 29);
+  // the caller says that the entries form a band (a problem the window kernel cannot take keeps the
+  // choice made above)
+  if (free_choice && banded && window_ok) variant = kSddmmWindow;
+  if (variant == kSddmmWindow && !window_ok) variant = kSddmmGroup;
   if (variant == kSddmmGroup && !fast_ok) variant = kSddmmRowstrip;
   const int avg = m > 0 ? nnz / m : 0;
   info->variant = variant;

@@ -443,6 +443,32 @@ def test_window_kernels_on_banded_masks(g, oracle_lib, force, n):
         assert np.array_equal(ob.cpu().numpy(), got)
 
 
+def test_banded_entry_points_fall_back_when_the_window_kernels_do_not_apply(g, oracle_lib):
+    """n % 4 != 0 (SpMM), dot products of more than 128 columns (SDDMM), a matrix without entries:
+    the entry points for banded masks then run what spdl_spmm / spdl_sddmm run."""
+    import torch
+    import paper_2006_10901_amd as spdl
+    A = wl.banded_attention_csr(300, 64, 0.4, 2200)
+    d = g.DevCsr(A)
+    for n in (130, 200):
+        B, L = wl.dense(A.k, n, 2201 + n), wl.dense(A.m, n, 2202 + n)
+        C, S = oracle_lib.spmm(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, B)
+        out, So = oracle_lib.sddmm(A.m, A.k, n, A.row_offsets, A.column_indices, L, B)
+        Cb = torch.full((A.m, n), float("nan"), device="cuda")
+        ob = torch.full((A.nnz,), float("nan"), device="cuda")
+        spdl.spdl_spmm_banded(A.m, A.k, n, A.nnz, d.ro, d.ci, d.val, g.dev(B), Cb)
+        spdl.spdl_sddmm_banded(A.m, A.k, n, A.nnz, d.ro, d.ci, g.dev(L), g.dev(B), ob)
+        torch.cuda.synchronize()
+        g.assert_close(Cb.cpu().numpy(), C, S, g.TOL_F32, f"spmm_banded n={n}")
+        g.assert_close(ob.cpu().numpy(), out, So, g.TOL_F32, f"sddmm_banded n={n}")
+    E = wl.Csr(40, 50, np.zeros(41, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.float32))
+    Ce = torch.full((40, 64), float("nan"), device="cuda")
+    none_i, none_f = torch.empty(0, dtype=torch.int32, device="cuda"), torch.empty(0, device="cuda")
+    spdl.spdl_spmm_banded(E.m, E.k, 64, 0, g.dev(E.row_offsets), none_i, none_f, torch.zeros((E.k, 64), device="cuda"), Ce)
+    torch.cuda.synchronize()
+    assert not Ce.cpu().numpy().any()
+
+
 # ------------------------------------------------------------------ matrix-core kernels (fp16)
 def _f16(A):
     A.values = A.values.astype(np.float16)
