@@ -224,10 +224,12 @@ def extra_cases(groups, wl, spdl, torch):
         dQ, dK, dV = dev(Q2), dev(K2), dev(V2)
         out2, C2 = torch.empty(A.nnz, device="cuda"), torch.empty((A.m, 128), device="cuda")
         extra.append(WidenedCase("attention_head_n128", "sddmm_banded", "window", A.nnz,
-                                 lambda: spdl.spdl_sddmm_banded(A.m, A.k, 128, A.nnz, ro, ci, dQ, dK, out2),
+                                 lambda A=A, ro=ro, ci=ci, dQ=dQ, dK=dK, out2=out2:
+                                 spdl.spdl_sddmm_banded(A.m, A.k, 128, A.nnz, ro, ci, dQ, dK, out2),
                                  sddmm_bytes(A.m, A.k, 128, A.nnz), 2.0 * A.nnz * 128, dims=(A.m, A.k, 128)))
         extra.append(WidenedCase("attention_head_n128", "spmm_banded", "window", A.nnz,
-                                 lambda: spdl.spdl_spmm_banded(A.m, A.k, 128, A.nnz, ro, ci, val, dV, C2),
+                                 lambda A=A, ro=ro, ci=ci, val=val, dV=dV, C2=C2:
+                                 spdl.spdl_spmm_banded(A.m, A.k, 128, A.nnz, ro, ci, val, dV, C2),
                                  spmm_bytes(A.m, A.k, 128, A.nnz), 2.0 * A.nnz * 128, dims=(A.m, A.k, 128)))
     if "conv_f16" in groups:                # sparse 1x1 convolution, fp16 in / fp32 accumulate
         for skew in (False, True):
