@@ -187,7 +187,7 @@ def widened_cases(wl, spdl, torch):
     return out
 
 
-EXTRA_GROUPS = ("ffn", "attention", "conv_f16", "conv_f32", "imbalance", "widened")
+EXTRA_GROUPS = ("ffn", "attention", "attention_n128", "conv_f16", "conv_f32", "imbalance", "widened")
 
 
 def extra_cases(groups, wl, spdl, torch):
@@ -213,6 +213,8 @@ def extra_cases(groups, wl, spdl, torch):
         w = wl.attention(0)
         extra.append(Case("attention_head", "sddmm", w["A"], 64, (w["Q"], w["K"]), spdl, torch))
         extra.append(Case("attention_head", "spmm", w["A"], 64, (w["V"],), spdl, torch))
+    if "attention_n128" in groups:
+        w = wl.attention(0)
         # The same mask with heads of 128 columns (hidden 1024 over 8 heads, paper Sec. "Application:
         # Sparse Transformer"): what spdl_spmm / spdl_sddmm choose from the shape alone, and the entry
         # points for banded masks, which the caller of an attention layer can name.
