@@ -998,6 +998,6 @@ const char* spdl_status_string(int status) {
   }
 }
 
-int spdl_version(void) { return 120; }
+int spdl_version(void) { return 130; }
 
 }  // extern "C"
