@@ -200,6 +200,9 @@ def test_spmm_selection_of_the_window_kernel(spdl):
         assert chosen(4096, 4096, 64, 0) == "rowsplit"            # nothing to fetch from
         assert chosen(64, 64, 130, 100) == "rowsplit"             # n % 4 != 0
         assert chosen(203, 700, 1028, 3000) == "window"
+        # 32-bit byte offsets into B: k * n * 4 < 2^31, else the general kernel
+        assert chosen(4096, 1 << 20, 256, 1 << 20) == "window"
+        assert chosen(4096, 1 << 20, 512, 1 << 20) == "rowsplit"
     finally:
         spdl.spdl_force_variant(0, -1)
 
@@ -222,6 +225,8 @@ def test_sddmm_selection_of_the_window_kernel(spdl):
         assert chosen(203, 700, 64, 3000) == "window"
         assert chosen(203, 700, 68, 3000) == "window"
         assert chosen(203, 700, 132, 3000) == "group"             # dot products of at most 128 columns
+        assert chosen(4096, 1 << 21, 128, 1 << 20) == "window"
+        assert chosen(4096, 1 << 22, 128, 1 << 20) == "group"     # k * n * 4 would reach 2^31
     finally:
         spdl.spdl_force_variant(1, -1)
 
