@@ -24,6 +24,7 @@
 #include "spmm_mfma.hpp"
 #include "spmm_slab_dma.hpp"
 #include "spmm_window.hpp"
+#include "spmm_slab_tiles.hpp"
 #include "sddmm_window.hpp"
 
 namespace {
@@ -114,13 +115,25 @@ int slab_rows_per_group(int m, int n) {
 constexpr int kSlabHalfS = 128;
 constexpr int kSlabHalfLdsBytes = 2 * (kSlabHalfS + 1) * kSlabTile * 4;
 
-void fill_spmm_slab_info(int m, int n, int variant, spdl_launch_info* info) {
+// The tile-inner slab kernel looks 48 pairs ahead per row: usable where the mean count of a row's
+// pairs in one slab plus three standard deviations fits into that (a row with more takes extra
+// rounds behind full waits in every tile's stage).
+inline bool slab_tiles_fits(int m, int k, int nnz) {
+  const double d = (m > 0 && k > 0) ? (double)nnz / ((double)m * (double)k) : 1.0;
+  const double mean = kSlabS * d;
+  return mean + 3.0 * std::sqrt(mean * std::max(0.0, 1.0 - d)) + 1.0 <= 48.0;
+}
+constexpr int kSlabTilesMax = 4;                  // tiles whose accumulators that kernel keeps in registers
+
+void fill_spmm_slab_info(int m, int k, int n, int nnz, int variant, spdl_launch_info* info) {
   const int tiles = (n + kSlabTile - 1) / kSlabTile;
   const bool half = variant == kSpmmSlabDma && (int64_t)((m + kSlabRows - 1) / kSlabRows) * tiles < kComputeUnits;
   const int rpg = (variant == kSpmmSlabDma && !half) ? slab_rows_per_group(m, n) : 1;
   const int rows = (half ? kSlabRows / 2 : kSlabRows) * rpg;
   const int panels = (m + rows - 1) / rows;
-  const int tpw = slab_tiles_per_wg(panels, tiles);
+  int tpw = slab_tiles_per_wg(panels, tiles);
+  // wide outputs, two rows per group: the tile-inner kernel, at most kSlabTilesMax tiles per workgroup
+  if (rpg == 2 && tpw >= 2 && slab_tiles_fits(m, k, nnz)) tpw = std::min(tpw, kSlabTilesMax);
   const int groups = (tiles + tpw - 1) / tpw;
   info->variant = variant;
   info->vec = 4;
@@ -244,7 +257,7 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
     info->grid_x = (m + info->rows_per_block - 1) / info->rows_per_block;
     info->grid_y = (n + kWinTile - 1) / kWinTile;
   } else if ((variant == kSpmmSlab || variant == kSpmmSlabDma) && sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C)) {
-    fill_spmm_slab_info(m, n, variant, info);
+    fill_spmm_slab_info(m, k, n, nnz, variant, info);
   } else {
     fill_spmm_rowsplit_info<T>(m, n, nnz, B, C, info);
   }
@@ -345,13 +358,19 @@ int spmm_impl(int m, int k, int n, int nnz, const int* ro, const I* ci, const T*
       // on the 70-90 % sparse shapes: the longer scan per round costs more than the waits it saves.
       const bool half = li.block_threads != kSlabThreads;
       const bool two_rows = li.rows_per_block == 2 * kSlabRows;
-      const void* dma_kernel = half       ? (const void*)spmm_slab_dma_kernel<kSlabHalfS, 1, 2, 8>
+      const void* dma_kernel_c = half       ? (const void*)spmm_slab_dma_kernel<kSlabHalfS, 1, 2, 8>
                                : two_rows ? (const void*)spmm_slab_dma_kernel<kSlabS, 2, 2>
                                           : (const void*)spmm_slab_dma_kernel<kSlabS, 1, 2>;
       const int lds = half ? kSlabHalfLdsBytes : kSlabLdsBytes;
+      const void* dma_kernel = dma_kernel_c;
+      // (two rows per group and 2 .. kSlabTilesMax tiles per workgroup: scanned once per slab for all tiles)
+      if (li.variant == kSpmmSlabDma && two_rows && li.grid_y >= 2 && li.grid_y <= kSlabTilesMax &&
+          slab_tiles_fits(m, k, nnz))
+        dma_kernel = (const void*)spmm_slab_tiles_kernel<kSlabS, 2, 3, kSlabTilesMax>;
       if (!configured.load()) {
         for (const void* f : {(const void*)kernel, (const void*)spmm_slab_dma_kernel<kSlabS, 1, 2>,
-                              (const void*)spmm_slab_dma_kernel<kSlabS, 2, 2>})
+                              (const void*)spmm_slab_dma_kernel<kSlabS, 2, 2>,
+                              (const void*)spmm_slab_tiles_kernel<kSlabS, 2, 3, kSlabTilesMax>})
           if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kSlabLdsBytes) != hipSuccess)
             return SPDL_ERR_LAUNCH;
         if (hipFuncSetAttribute((const void*)spmm_slab_dma_kernel<kSlabHalfS, 1, 2, 8>,

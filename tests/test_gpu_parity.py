@@ -469,6 +469,53 @@ def test_banded_entry_points_fall_back_when_the_window_kernels_do_not_apply(g, o
     assert not Ce.cpu().numpy().any()
 
 
+def _with_dense_rows(A, rows, seed):
+    """A copy of A in which the given rows hold every column."""
+    rng = np.random.default_rng(seed)
+    lens = np.diff(A.row_offsets).astype(np.int64)
+    lens[sorted(rows)] = A.k
+    ro = np.zeros(A.m + 1, dtype=np.int64)
+    np.cumsum(lens, out=ro[1:])
+    ci = np.empty(ro[-1], dtype=np.int32)
+    for i in range(A.m):
+        ci[ro[i]:ro[i + 1]] = (np.arange(A.k) if i in rows
+                               else A.column_indices[A.row_offsets[i]:A.row_offsets[i + 1]])
+    return wl.Csr(A.m, A.k, ro.astype(np.int32), ci, rng.standard_normal(int(ro[-1])).astype(np.float32))
+
+
+def test_spmm_wide_outputs_tile_inner_slab_kernel(g, oracle_lib, force):
+    """Outputs wide enough for two rows per lane group and several tiles per workgroup: the slab
+    kernel that scans a slab once for all its tiles.  A ragged last tile, a density at the edge of
+    its look-ahead, rows that hold every column (more pairs in a slab than one scan takes: extra
+    rounds in every tile's stage), rows that are not ascending, with and without a row order, and the
+    fused bias + ReLU."""
+    import torch
+    import paper_2006_10901_amd as spdl
+    cases = [(wl.uniform_mask_csr(2048, 700, 0.10, 2300), 2000),
+             (wl.uniform_mask_csr(2048, 1300, 0.12, 2301), 2052),
+             (_with_dense_rows(wl.uniform_mask_csr(2048, 900, 0.08, 2302), {0, 77, 1029, 2047}, 2303), 2304),
+             (wl.adversarial_csr(2100, 600, 2304, sorted_cols=False), 2500)]
+    slabdma = [v for v in spmm_variants() if spdl.spdl_variant_name(0, v) == "slabdma"][0]
+    force(0, slabdma)            # (the very sparse last case would otherwise take the gather kernel)
+    for idx, (A, n) in enumerate(cases):
+        B = wl.dense(A.k, n, 2310 + idx)
+        sel = spdl.spdl_select_spmm(A.m, A.k, n, A.nnz, 4, 0, 0)
+        assert sel["variant"] == slabdma and sel["rows_per_block"] == 128
+        assert 2 <= sel["grid_y"] <= 4
+        C, S = oracle_lib.spmm(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, B)
+        for order in (None, spdl.spdl_build_row_order(A.m, A.row_offsets)):
+            g.assert_close(g.gpu_spmm(A, B, n, order), C, S, g.TOL_F32, f"tile-inner slab case {idx}")
+    A, n = cases[0]
+    B = wl.dense(A.k, n, 2310)
+    bias = np.random.default_rng(2320).standard_normal(A.m).astype(np.float32)
+    C, S = oracle_lib.spmm_bias_relu(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, B, bias, True)
+    d = g.DevCsr(A)
+    out = torch.full((A.m, n), float("nan"), device="cuda")
+    spdl.spdl_spmm_bias_relu(A.m, A.k, n, A.nnz, d.ro, d.ci, d.val, None, g.dev(B), g.dev(bias), 1, out)
+    torch.cuda.synchronize()
+    g.assert_close(out.cpu().numpy(), C, S, g.TOL_F32, "tile-inner slab, bias + ReLU")
+
+
 # ------------------------------------------------------------------ matrix-core kernels (fp16)
 def _f16(A):
     A.values = A.values.astype(np.float16)

@@ -231,6 +231,19 @@ def test_sddmm_selection_of_the_window_kernel(spdl):
         spdl.spdl_force_variant(1, -1)
 
 
+def test_spmm_tile_inner_slab_kernel_shape(spdl):
+    """Wide outputs with two rows per lane group walk at most four tiles per workgroup (their
+    accumulators stay in registers while a slab is scanned once for all of them), unless a slab holds
+    more of a row than the 48 pairs of look-ahead (mean + 3 sigma)."""
+    s = spdl.spdl_select_spmm(4096, 1024, 4096, 420757, 4, 0, 0)            # Transformer W1, 10 % dense
+    assert spdl.spdl_variant_name(0, s["variant"]) == "slabdma"
+    assert (s["rows_per_block"], s["grid_y"], s["grid_x"]) == (128, 4, 512)
+    s = spdl.spdl_select_spmm(1024, 4096, 4096, 420099, 4, 0, 0)            # W2: two tiles fill the machine
+    assert (s["rows_per_block"], s["grid_y"]) == (128, 2)
+    s = spdl.spdl_select_spmm(4096, 1024, 4096, int(4096 * 1024 * 0.3), 4, 0, 0)   # 77 pairs per slab: the other kernel
+    assert (s["rows_per_block"], s["grid_y"]) == (128, 8)
+
+
 def test_forced_slab_variants_never_run_an_empty_matrix(spdl):
     """With nnz == 0 the sparse arrays and B may be null; the kernels that fetch from them
     unconditionally must not be chosen, forced or not."""
