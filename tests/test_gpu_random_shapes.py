@@ -1,0 +1,88 @@
+"""GPU parity on seeded random shapes: sizes, output widths, densities and row-length
+distributions drawn at random (none of them a multiple of any tile on purpose), fp32 and fp16,
+the kernel chosen by default or forced at random, SpMM and SDDMM through the C ABI against the
+CPU oracle element by element.  The hand-picked cases of the other files aim at known boundaries;
+this one looks for the combinations nobody thought of."""
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+WIDTHS = [1, 4, 8, 16, 24, 32, 48, 64, 72, 96, 128, 136, 192, 200, 256, 320, 512, 1000, 2048]
+
+
+@pytest.fixture(scope="module")
+def g():
+    import torch
+    assert torch.cuda.is_available(), "the gpu tests need a GPU"
+    from tests import gpu_util
+    return gpu_util
+
+
+def draw_case(rng):
+    """One problem: shape, matrix, precision.  The oracle's work is bounded to a few GFLOP."""
+    big = rng.random() < 0.5
+    m = int(rng.integers(1, 20000 if big else 1500))
+    k = int(rng.integers(1, 8192 if big else 1500))
+    n = int(rng.choice(WIDTHS))
+    density = float(np.exp(rng.uniform(np.log(0.003), np.log(0.6))))
+    while 2.0 * m * k * density * n > 3e9:
+        if n > 64 and rng.random() < 0.5:
+            n //= 2
+        else:
+            density *= 0.6
+    kind = int(rng.integers(0, 4))
+    seed = int(rng.integers(1, 1 << 30))
+    f16 = bool(rng.random() < 0.3)
+    if kind == 0:
+        A = wl.uniform_mask_csr(m, k, density, seed)
+    elif kind == 1:
+        A = wl.lognormal_rows_csr(m, k, density, seed)
+    elif kind == 2:
+        A = wl.binomial_rows_csr(m, k, density, seed)
+    else:
+        A = wl.adversarial_csr(min(m, 3000), k, seed, sorted_cols=bool(rng.integers(0, 2)))
+    if f16:
+        A.values = A.values.astype(np.float16)
+    return A, n, seed, f16, ("uniform", "lognormal", "binomial", "adversarial")[kind]
+
+
+@pytest.mark.parametrize("stream_seed", [11, 12, 13])
+def test_random_shapes_default_and_forced_kernels(g, oracle_lib, stream_seed):
+    import paper_2006_10901_amd as spdl
+    rng = np.random.default_rng(stream_seed)
+    n_spmm = sum(1 for v in range(16) if spdl.spdl_variant_name(0, v) is not None)
+    n_sddmm = sum(1 for v in range(16) if spdl.spdl_variant_name(1, v) is not None)
+    ran = set()
+    try:
+        for it in range(60):
+            A, n, seed, f16, kind = draw_case(rng)
+            m, k = A.m, A.k
+            # (a forced kernel that cannot run the problem falls back to one that can)
+            fs = int(rng.integers(0, n_spmm)) if rng.random() < 0.6 else -1
+            fd = int(rng.integers(0, n_sddmm)) if rng.random() < 0.6 else -1
+            spdl.spdl_force_variant(0, fs)
+            spdl.spdl_force_variant(1, fd)
+            es = 2 if f16 else 4
+            sp = spdl.spdl_variant_name(0, spdl.spdl_select_spmm(m, k, n, A.nnz, es, 0, 0)["variant"])
+            sd = spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(m, k, n, A.nnz, es, 0, 0)["variant"])
+            what = (f"stream {stream_seed} case {it}: m={m} k={k} n={n} nnz={A.nnz} {kind} seed={seed} "
+                    f"{'f16' if f16 else 'f32'} spmm={sp} sddmm={sd}")
+            print(what, flush=True)
+            ran.update({("spmm", sp), ("sddmm", sd)})
+            dt = np.float16 if f16 else np.float32
+            tol = g.TOL_F16 if f16 else g.TOL_F32
+            B = wl.dense(k, n, seed + 1, dt)
+            C, S = oracle_lib.spmm(m, k, n, A.row_offsets, A.column_indices, A.values, B)
+            order = spdl.spdl_build_row_order(m, A.row_offsets) if rng.random() < 0.5 else None
+            g.assert_close(g.gpu_spmm(A, B, n, order), C, S, tol, "spmm, " + what)
+            L, R = wl.dense(m, n, seed + 2, dt), wl.dense(k, n, seed + 3, dt)
+            out, S = oracle_lib.sddmm(m, k, n, A.row_offsets, A.column_indices, L, R)
+            g.assert_close(g.gpu_sddmm(A, L, R, n), out, S, tol, "sddmm, " + what)
+    finally:
+        spdl.spdl_force_variant(0, -1)
+        spdl.spdl_force_variant(1, -1)
+    # the draw reaches the families it is meant to reach
+    assert {("spmm", "rowsplit"), ("spmm", "slabdma"), ("sddmm", "group"), ("sddmm", "slabdma")} <= ran
