@@ -86,3 +86,105 @@ def test_random_shapes_default_and_forced_kernels(g, oracle_lib, stream_seed):
         spdl.spdl_force_variant(1, -1)
     # the draw reaches the families it is meant to reach
     assert {("spmm", "rowsplit"), ("spmm", "slabdma"), ("sddmm", "group"), ("sddmm", "slabdma")} <= ran
+
+
+def draw_banded(rng, n):
+    """A square attention mask: dense band (two-sided or causal) plus decaying scatter."""
+    seq = int(rng.integers(100, 9000))
+    band = min(int(rng.integers(1, 400)), seq // 4)
+    off = float(rng.uniform(0.0, 0.15))
+    while 2.0 * seq * (band + seq * off) * n > 3e9:
+        off *= 0.5
+    seed = int(rng.integers(1, 1 << 30))
+    if rng.random() < 0.5:
+        return wl.banded_attention_csr(seq, band, min(0.9, (band + 2) / seq + off + 0.002), seed), seed, "banded"
+    return wl.causal_attention_csr(seq, band, off, seed), seed, "causal"
+
+
+@pytest.mark.parametrize("stream_seed", [21, 22])
+def test_random_shapes_entry_points_around_spmm_and_sddmm(g, oracle_lib, stream_seed):
+    """The same draw through the other entry points: bias + ReLU epilogue, SDDMM scaled by the
+    stored values, SDDMM with the right-hand operand not transposed, fp16 SpMM with 16-bit column
+    indices, the entry points for banded masks on random band / scatter mixes, softmax over rows."""
+    import torch
+    import paper_2006_10901_amd as spdl
+    rng = np.random.default_rng(stream_seed)
+    n_spmm = sum(1 for v in range(16) if spdl.spdl_variant_name(0, v) is not None)
+    n_sddmm = sum(1 for v in range(16) if spdl.spdl_variant_name(1, v) is not None)
+
+    def fresh(shape, dtype):
+        return torch.full(shape, float("nan"), dtype=dtype, device="cuda")    # must be fully overwritten
+
+    try:
+        for it in range(60):
+            op = ("bias_relu", "scaled", "nt", "int16", "banded", "softmax")[int(rng.integers(0, 6))]
+            if op == "banded":
+                n = int(rng.choice([8, 36, 64, 100, 128, 200]))
+                A, seed, kind = draw_banded(rng, n)
+                f16 = False
+            else:
+                A, n, seed, f16, kind = draw_case(rng)
+            m, k = A.m, A.k
+            f16 = f16 or op == "int16"
+            A.values = A.values.astype(np.float16 if f16 else np.float32)
+            spdl.spdl_force_variant(0, int(rng.integers(0, n_spmm)) if rng.random() < 0.5 else -1)
+            spdl.spdl_force_variant(1, int(rng.integers(0, n_sddmm)) if rng.random() < 0.5 else -1)
+            what = f"stream {stream_seed} case {it}: {op} m={m} k={k} n={n} nnz={A.nnz} {kind} seed={seed} {'f16' if f16 else 'f32'}"
+            print(what, flush=True)
+            dt, tdt = (np.float16, torch.float16) if f16 else (np.float32, torch.float32)
+            tol = g.TOL_F16 if f16 else g.TOL_F32
+            d = g.DevCsr(A)
+            order = spdl.spdl_build_row_order(m, A.row_offsets) if rng.random() < 0.5 else None
+            dorder = None if order is None else g.dev(order)
+            a32 = A.values.astype(np.float32)
+            if op in ("bias_relu", "int16", "banded"):
+                B = wl.dense(k, n, seed + 1, dt)
+                out = fresh((m, n), tdt)
+                if op == "bias_relu":
+                    bias = np.random.default_rng(seed + 5).standard_normal(m).astype(dt) if rng.random() < 0.7 else None
+                    relu = bool(rng.integers(0, 2))
+                    # (binary16 -> binary32 is exact, so the fp32 oracle on widened inputs is the fp16 oracle)
+                    C, S = oracle_lib.spmm_bias_relu(m, k, n, A.row_offsets, A.column_indices, a32, B.astype(np.float32),
+                                                     None if bias is None else bias.astype(np.float32), relu)
+                    fn = spdl.spdl_spmm_bias_relu_f16 if f16 else spdl.spdl_spmm_bias_relu
+                    fn(m, k, n, A.nnz, d.ro, d.ci, d.val, dorder, g.dev(B), None if bias is None else g.dev(bias), relu, out)
+                else:
+                    C, S = oracle_lib.spmm(m, k, n, A.row_offsets, A.column_indices, A.values, B)
+                    if op == "int16":
+                        spdl.spdl_spmm_f16_i16(m, k, n, A.nnz, d.ro, g.dev(A.column_indices.astype(np.int16)), d.val,
+                                               dorder, g.dev(B), out)
+                    else:
+                        spdl.spdl_spmm_banded(m, k, n, A.nnz, d.ro, d.ci, d.val, g.dev(B), out)
+                torch.cuda.synchronize()
+                g.assert_close(out.cpu().numpy(), C, S, tol, what)
+            if op in ("scaled", "nt", "banded"):
+                L, R = wl.dense(m, n, seed + 2, dt), wl.dense(k, n, seed + 3, dt)
+                ref, S = oracle_lib.sddmm(m, k, n, A.row_offsets, A.column_indices, L, R)
+                out = fresh((A.nnz,), tdt)
+                v = np.ones(A.nnz)
+                if op == "scaled":
+                    fn = spdl.spdl_sddmm_scaled_f16 if f16 else spdl.spdl_sddmm_scaled
+                    fn(m, k, n, A.nnz, d.ro, d.ci, d.val, g.dev(L), g.dev(R), out)
+                    v = A.values.astype(np.float64)
+                elif op == "nt":
+                    scaled = bool(rng.integers(0, 2))
+                    fn = spdl.spdl_sddmm_nt_f16 if f16 else spdl.spdl_sddmm_nt
+                    fn(m, k, n, A.nnz, d.ro, d.ci, d.val if scaled else None, g.dev(L), g.dev(np.ascontiguousarray(R.T)), out)
+                    v = A.values.astype(np.float64) if scaled else v
+                else:
+                    spdl.spdl_sddmm_banded(m, k, n, A.nnz, d.ro, d.ci, g.dev(L), g.dev(R), out)
+                torch.cuda.synchronize()
+                g.assert_close(out.cpu().numpy(), v * ref, np.abs(v) * S, tol, what)
+            if op == "softmax":
+                x = (3.0 * np.random.default_rng(seed).standard_normal(A.nnz)).astype(np.float32)
+                scale = float(rng.uniform(0.05, 2.0))
+                ref = oracle_lib.csr_softmax(m, A.row_offsets, x, scale)
+                out = fresh((A.nnz,), torch.float32)
+                spdl.spdl_csr_softmax(m, A.nnz, d.ro, g.dev(x), scale, out)
+                torch.cuda.synchronize()
+                got = out.cpu().numpy().astype(np.float64)
+                assert np.all(np.isfinite(got)), what
+                assert (np.abs(got - ref) <= 1e-4 * ref + 1e-37).all(), what
+    finally:
+        spdl.spdl_force_variant(0, -1)
+        spdl.spdl_force_variant(1, -1)
