@@ -211,16 +211,19 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
 
   // rows of this group, their ranges of nonzeros inside [k0, k1), their quarters of L in the
   // order of use: lr[j][8 s + e] = L[row, 32 h + 8((t-s) mod 4) + e]
-  // the first slab is requested before anything else: it depends on nothing that follows
-  if constexpr (NT) fetch_slab_nt(0);
-  else copy_stage(0);
-
+  //
+  // Vector-memory loads return in order, and every workgroup of the launch starts at the same time:
+  // whatever is requested behind the first slab and the rows of L (20 MB over the whole chip on the
+  // LSTM shape) waits for that burst.  The chain of dependent loads (row offsets, then the rounds of
+  // the searches) therefore goes first, while the memory system is idle, and the bulk (first slab,
+  // L, first look-ahead) is requested in one go behind it.
   int row[RPG], p_end[RPG], p[RPG];
   float lr[RPG][32];
+  f32x4 lraw[RPG][2];                // piece t of quarter h of the rows of L, as loaded
+  bool lok[RPG];
   bool safe = true;                  // no load of the look-ahead can pass the end of the arrays
   {
-    // Everything the set-up reads is requested before anything is waited for: the row offsets of all
-    // rows, then the quarters of L (raw), then the searches for the rows' ranges inside [k0, k1), all
+    // The row offsets of all rows, then the searches for the rows' ranges inside [k0, k1), all
     // 2*RPG of them side by side (a round of probes costs one memory latency, not 2*RPG).
     int rb[RPG], re[RPG];
     bool ok[RPG];
@@ -239,18 +242,6 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
       rb[j] = ok[j] ? row_offsets[r] : 0;
       re[j] = ok[j] ? row_offsets[r + 1] : 0;
     }
-    f32x4 raw[RPG][8];
-#pragma unroll
-    for (int j = 0; j < RPG; ++j) {
-      const float* lrow = L + (size_t)max(row[j], 0) * ld;
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const int c = 32 * h4 + 8 * ((t4 - s) & 3) + 4 * u;
-          raw[j][2 * s + u] = *reinterpret_cast<const f32x4*>(lrow + (c < n ? c : 0));
-        }
-    }
     int lo[2 * RPG], hi[2 * RPG], key[2 * RPG];
 #pragma unroll
     for (int j = 0; j < RPG; ++j) {
@@ -261,24 +252,24 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
       hi[2 * j + 1] = re[j];
       key[2 * j + 1] = k1;
     }
-    sd_lower_bound16_batch<2 * RPG>(column_indices, lo, hi, key, sub, l16, last_nz);
+    sd_lower_bound16_batch<2 * RPG>(column_indices, lo, hi, key, sub, l16, last_nz, k);
+    if constexpr (NT) fetch_slab_nt(0);
+    else copy_stage(0);
 #pragma unroll
     for (int j = 0; j < RPG; ++j) {
       p[j] = lo[2 * j];
       p_end[j] = max(lo[2 * j + 1], p[j]);
       safe = safe && __builtin_amdgcn_ballot_w64(p_end[j] + WIN > nnz) == 0;
+      // Every lane loads the 32 bytes it uses in step 0 (piece t of quarter h); the pieces of the
+      // other steps come from the lanes that loaded them, by row rotations (below): a quarter of the
+      // load instructions of fetching all four pieces in every lane.
+      const float* lrow = L + (size_t)max(row[j], 0) * ld;
+      lok[j] = ok[j];
 #pragma unroll
-      for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const int c = 32 * h4 + 8 * ((t4 - s) & 3) + 4 * u;
-          const bool in = ok[j] && c < n;
-          const f32x4 vv = raw[j][2 * s + u];
-          lr[j][8 * s + 4 * u + 0] = in ? vv.x : 0.f;
-          lr[j][8 * s + 4 * u + 1] = in ? vv.y : 0.f;
-          lr[j][8 * s + 4 * u + 2] = in ? vv.z : 0.f;
-          lr[j][8 * s + 4 * u + 3] = in ? vv.w : 0.f;
-        }
+      for (int u = 0; u < 2; ++u) {
+        const int c = 32 * h4 + 8 * t4 + 4 * u;
+        lraw[j][u] = *reinterpret_cast<const f32x4*>(lrow + (c < n ? c : 0));
+      }
     }
   }
   // byte offset of step s from the start of an R row in region 0: this lane's region, its half of
@@ -341,6 +332,24 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
 
 #pragma unroll
   for (int j = 0; j < RPG; ++j) fetch(j, p[j]);
+  // lr[j][8 s + e]: the piece that lane (t - s, h) loaded, i.e. the lane 4 s places to the left in
+  // the group (row_ror:4s moves lane i - 4 s to lane i); columns past n and rows past m count as zero.
+#pragma unroll
+  for (int j = 0; j < RPG; ++j)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const bool in = lok[j] && 32 * h4 + 8 * t4 + 4 * u < n;
+      const f32x4 vv = lraw[j][u];
+      const float own[4] = {in ? vv.x : 0.f, in ? vv.y : 0.f, in ? vv.z : 0.f, in ? vv.w : 0.f};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int bits = __builtin_bit_cast(int, own[e]);
+        lr[j][4 * u + e] = own[e];
+        lr[j][8 + 4 * u + e] = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, bits, 0x124 /* row_ror:4 */, 0xf, 0xf, false));
+        lr[j][16 + 4 * u + e] = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, bits, 0x128 /* row_ror:8 */, 0xf, 0xf, false));
+        lr[j][24 + 4 * u + e] = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, bits, 0x12c /* row_ror:12 */, 0xf, 0xf, false));
+      }
+    }
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   if constexpr (NT) {
@@ -355,6 +364,11 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
     const int row_base = buf_off - slab_start * 256;
     bool first = true, more;
     do {
+      // Wave priorities by phase: the waves of a SIMD that are furthest behind in the stage go first
+      // (counting before the first row's strips before the second row's), so that they reach the
+      // barrier together instead of one after the other, the last of them alone on its SIMD with
+      // nothing to cover its LDS latencies.
+      __builtin_amdgcn_s_setprio(3);
       // A use of every look-ahead register before the copies are issued: the compiler places its
       // wait for those loads here, where they completed long ago (full wait at the end of the
       // previous stage), instead of after the copies, where it would wait for those too.
@@ -421,6 +435,8 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
       }
 #pragma unroll
       for (int j = 0; j < RPG; ++j) {
+        if (j == 0) __builtin_amdgcn_s_setprio(2);
+        else __builtin_amdgcn_s_setprio(1);
         // Software pipeline over (strip, step): LDS reads run two steps ahead of the
         // multiply-adds, also across strips, through two register sets used in turn; reads
         // for a strip that does not exist hit a valid address and are dropped.
@@ -470,6 +486,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
           st_mask[j][i] = okm[j][i];
         }
       }
+      __builtin_amdgcn_s_setprio(0);
       if (more) __builtin_amdgcn_s_waitcnt(0);       // a row has more than 16*NCHD nonzeros in this slab
     } while (more);
     __builtin_amdgcn_s_waitcnt(0);
@@ -487,10 +504,14 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
 #pragma unroll
   for (int j = 0; j < RPG; ++j)
     if (p[j] != p_end[j] && row[j] >= 0) {
+      // (the same searches as in the set-up: for a row that is not ascending only the same procedure
+      // gives the same range, and the ranges of the column parts have to tile the row)
       const int rb = row_offsets[row[j]], re = row_offsets[row[j] + 1];
-      const int b0 = k0 <= 0 ? rb : sd_lower_bound16(column_indices, rb, re, k0, sub, l16, last_nz);
-      int e = k1 >= k ? re : sd_lower_bound16(column_indices, rb, re, k1, sub, l16, last_nz);
-      e = max(e, b0);
+      int lo2[2] = {rb, k1 >= k ? re : rb}, hi2[2] = {k0 <= 0 ? rb : re, re};
+      const int key2[2] = {k0, k1};
+      sd_lower_bound16_batch<2>(column_indices, lo2, hi2, key2, sub, l16, last_nz, k);
+      const int b0 = lo2[0];
+      const int e = max(lo2[1], b0);
       if constexpr (NT) {
         // one lane per stored entry, the plain definition
         for (int t = b0 + l16; t < e; t += 16) {

@@ -58,9 +58,49 @@ __device__ __forceinline__ int sd_lower_bound16(const int* __restrict__ ci, int 
 // NB such searches at once (lo[b], hi[b], key[b]; the result is left in lo[b]): the probes of all
 // of them are loaded before any is looked at, so a round costs one memory latency however many
 // searches there are.  A search with lo == hi is already finished.
+//
+// kcols > 0 (the number of columns of A) adds a first round that looks where the bound would be if
+// the row's columns were spread evenly: sixteen probes around lo + len * key / kcols, spaced so that
+// they span about eight standard deviations of that position for a random row.  Where the bound
+// lies between two of them, a second round finishes the search for rows of up to a few thousand
+// entries (three rounds without); where it does not, the round still halves nothing worse than the
+// side it excludes, and the plain rounds go on from there.  Every round is a memory latency that
+// the whole workgroup waits for before its first slab.
 template <int NB>
 __device__ __forceinline__ void sd_lower_bound16_batch(const int* __restrict__ ci, int (&lo)[NB], int (&hi)[NB],
-                                                       const int (&key)[NB], int sub, int l16, int last_nz) {
+                                                       const int (&key)[NB], int sub, int l16, int last_nz,
+                                                       int kcols = 0) {
+  bool any_open = false;
+#pragma unroll
+  for (int b = 0; b < NB; ++b) any_open = any_open || hi[b] > lo[b];
+  if (kcols > 0 && __any(any_open)) {
+    int v[NB], g0[NB], sp[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const int len = hi[b] - lo[b];
+      const float f = (float)key[b] / (float)kcols;
+      const float var = (float)len * f * (1.f - f);
+      sp[b] = (int)(0.5f * __builtin_sqrtf(var > 0.f ? var : 0.f)) + 1;
+      g0[b] = lo[b] + (int)((float)len * f) - ((15 * sp[b]) >> 1);
+      const int probe = min(max(g0[b] + l16 * sp[b], lo[b]), max(hi[b] - 1, lo[b]));
+      v[b] = ci[min(max(probe, 0), last_nz)];
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const int len = hi[b] - lo[b];
+      const bool less = len > 0 && v[b] < key[b];
+      const unsigned long long mask = __ballot(less);
+      const unsigned piece = (unsigned)(mask >> (sub * 16)) & 0xffffu;
+      const int cnt = __builtin_ctz(~piece | 0x10000u);
+      const int top = max(hi[b] - 1, lo[b]);
+      const int below = min(max(g0[b] + (cnt - 1) * sp[b], lo[b]), top);      // last probe found less
+      const int at = min(max(g0[b] + cnt * sp[b], lo[b]), top);               // first probe found not less
+      const int nlo = cnt > 0 ? below + 1 : lo[b];
+      const int nhi = cnt < 16 ? at : hi[b];
+      lo[b] = len > 0 ? nlo : lo[b];
+      hi[b] = len > 0 ? max(nhi, nlo) : hi[b];
+    }
+  }
   while (true) {
     bool open = false;
 #pragma unroll
