@@ -93,9 +93,13 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_slab_dma_kernel(
     r.row = row < m ? row : -1;
     const int rb = row < m ? row_offsets[row] : 0;
     r.row_end = row < m ? row_offsets[row + 1] : 0;
-    r.p_start = k0 <= 0 ? rb : sd_lower_bound16(column_indices, rb, r.row_end, k0, sub, l16, last_nz);
-    r.p_end = k1 >= k ? r.row_end : sd_lower_bound16(column_indices, rb, r.row_end, k1, sub, l16, last_nz);
-    r.p_end = max(r.p_end, r.p_start);
+    // both ends of the range side by side, the first round of probes placed by interpolation: two
+    // memory latencies before the first slab instead of six
+    int lo[2] = {rb, k1 >= k ? r.row_end : rb}, hi[2] = {k0 <= 0 ? rb : r.row_end, r.row_end};
+    const int key[2] = {k0, k1};
+    sd_lower_bound16_batch<2>(column_indices, lo, hi, key, sub, l16, last_nz, k);
+    r.p_start = lo[0];
+    r.p_end = max(lo[1], r.p_start);
     r.p = r.p_start;
     sd_fetch<DEFERRED>(r, l16, last_nz, column_indices);
   }
