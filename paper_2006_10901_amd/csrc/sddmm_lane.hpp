@@ -69,9 +69,11 @@ constexpr int kLaneLdsBytes = 2 * kLaneBuf;
 constexpr int kLanePairBytes = 1024 + 32;
 constexpr int kLaneNtLdsBytes = kLaneBuf + 64 * kLanePairBytes;
 
-// The two 16-byte LDS reads of one step: 32 bytes of the R row at byte offset `off`, from x on.
-__device__ __forceinline__ void lane_read(const char* lds, int off, int x, f32x4& b0, f32x4& b1) {
-  const char* a = lds + (off + x);
+// The two 16-byte LDS reads of one step: 32 bytes of the R row at byte offset `off`, from the
+// lane's position `at` (start of LDS + the step's offset inside a row, formed once) on: one
+// address addition per step.
+__device__ __forceinline__ void lane_read(const char* at, int off, f32x4& b0, f32x4& b1) {
+  const char* a = at + off;
   b0 = *reinterpret_cast<const f32x4*>(a);
   b1 = *reinterpret_cast<const f32x4*>(a + 16);
 }
@@ -274,9 +276,9 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
   }
   // byte offset of step s from the start of an R row in region 0: this lane's region, its half of
   // the 256-byte row, and the rotated 32-byte piece
-  int x[4];
+  const char* x[4];
 #pragma unroll
-  for (int s = 0; s < 4; ++s) x[s] = (h4 >> 1) * kLaneRegion + (h4 & 1) * 128 + ((t4 - s) & 3) * 32;
+  for (int s = 0; s < 4; ++s) x[s] = lds_raw + ((h4 >> 1) * kLaneRegion + (h4 & 1) * 128 + ((t4 - s) & 3) * 32);
 
   // Look-ahead of row j from position `from`: the next 16*NCHD column indices, lane 4t+h of the
   // group holding index 16 i + 4 h + t of chunk i; with them the values of A if the results are
@@ -450,8 +452,8 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
         };
         f32x4 b[2][2];
         int off = strip_off(0, 0);
-        lane_read(lds_raw, off, x[0], b[0][0], b[0][1]);
-        lane_read(lds_raw, off, x[1], b[1][0], b[1][1]);
+        lane_read(x[0], off, b[0][0], b[0][1]);
+        lane_read(x[1], off, b[1][0], b[1][1]);
         bool done = false;
 #pragma unroll
         for (int i = 0; i < NCHD; ++i) {
@@ -475,8 +477,8 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
               acc1 = __builtin_fmaf(l[5], b1.y, acc1);
               acc0 = __builtin_fmaf(l[6], b1.z, acc0);
               acc1 = __builtin_fmaf(l[7], b1.w, acc1);
-              if (st < 2) lane_read(lds_raw, off, x[st + 2], b[st & 1][0], b[st & 1][1]);
-              else if (!last_strip) lane_read(lds_raw, off_next, x[st - 2], b[st & 1][0], b[st & 1][1]);
+              if (st < 2) lane_read(x[st + 2], off, b[st & 1][0], b[st & 1][1]);
+              else if (!last_strip) lane_read(x[st - 2], off_next, b[st & 1][0], b[st & 1][1]);
             }
             const float total = quad_sum(acc0 + acc1);
             keep = h4 == q ? total : keep;
