@@ -363,6 +363,26 @@ def test_forced_sddmm_variants_ragged(g, oracle_lib, force, n):
             g.assert_close(got, out, S, g.TOL_F32, f"sddmm variant {spdl.spdl_variant_name(1, v)} n={n}")
 
 
+@pytest.mark.parametrize("shape", [(700, 4100, 128), (333, 1500, 100), (200, 9000, 68), (130, 640, 264)])
+def test_sddmm_column_parts_on_rows_with_clustered_columns(g, oracle_lib, force, shape):
+    """The slab kernels split A's columns over workgroups and find where each part of a row starts by
+    a search whose first probes are placed by interpolation, as if the row's columns were spread
+    evenly.  Rows whose columns are clustered at one end, at both ends, around a random centre or
+    run with gaps are where that guess is wrong by as much as it can be: every variant against the
+    oracle."""
+    import paper_2006_10901_amd as spdl
+    m, k, n = shape
+    A = wl.clustered_rows_csr(m, k, 7000 + m)
+    L, R = wl.dense(m, n, 7001 + m), wl.dense(k, n, 7002 + m)
+    ref, S = oracle_lib.sddmm(A.m, A.k, n, A.row_offsets, A.column_indices, L, R)
+    for v in sddmm_variants():
+        if spdl.spdl_variant_name(1, v) == "mfma":
+            continue
+        force(1, v)
+        g.assert_close(g.gpu_sddmm(A, L, R, n), ref, S, g.TOL_F32,
+                       f"clustered columns, sddmm variant {spdl.spdl_variant_name(1, v)}, shape {shape}")
+
+
 @pytest.mark.parametrize("n", [132, 256, 388])
 def test_sddmm_long_dot_products_of_dense_rows(g, oracle_lib, n):
     """Rows too dense for the slab kernel's 32 partial sums per row and slab, dot products longer

@@ -150,6 +150,37 @@ def causal_attention_csr(seq, band, off_density, seed, sigma=1.0) -> Csr:
     return Csr(seq, seq, ro.astype(np.int32), cc.astype(np.int32), vals)
 
 
+def clustered_rows_csr(m, k, seed, sigma=1.0) -> Csr:
+    """Rows whose columns are anything but evenly spread over [0, k): each row draws a pattern at
+    random: all columns in a narrow range at the left end, at the right end or around a random
+    centre; two clusters at both ends; every second row of a dense run; or spread evenly.  Columns
+    ascending inside a row.  (A test input for searches that guess positions by interpolation.)"""
+    rng = np.random.default_rng(seed)
+    rows = []
+    for _ in range(m):
+        kind = int(rng.integers(0, 6))
+        width = int(rng.integers(1, max(2, k // 8)))
+        if kind == 0:
+            pool = np.arange(0, min(k, width))
+        elif kind == 1:
+            pool = np.arange(max(0, k - width), k)
+        elif kind == 2:
+            c = int(rng.integers(0, k))
+            pool = np.arange(max(0, c - width // 2), min(k, c + width // 2 + 1))
+        elif kind == 3:
+            pool = np.concatenate([np.arange(0, min(k // 2, width)), np.arange(max(k // 2, k - width), k)])
+        elif kind == 4:
+            c = int(rng.integers(0, max(1, k - 2 * width)))
+            pool = np.arange(c, min(k, c + 2 * width), 2)
+        else:
+            pool = np.arange(k)
+        take = int(rng.integers(0, len(pool) + 1))
+        if rng.random() < 0.3:
+            take = len(pool)
+        rows.append(np.sort(rng.choice(pool, size=take, replace=False)).astype(np.int32))
+    return _from_mask_rows(m, k, rows, rng, sigma)
+
+
 def dense(rows, cols, seed, dtype=np.float32) -> np.ndarray:
     rng = np.random.default_rng(seed)
     x = rng.standard_normal((rows, cols), dtype=np.float32)
