@@ -35,6 +35,21 @@ def build_microbench(verbose: bool = False) -> str:
     return MICROBENCH_BIN
 
 
+CLOCKS_LIB_PATH = os.path.join(_HERE, "microbench", "libspdl_phase_clocks.so")
+
+
+def build_phase_clocks(verbose: bool = False) -> str:
+    """A second copy of the library with clocks compiled into the slab kernels
+    (-DSPDL_PHASE_CLOCKS), for microbench/phase_clocks.py only; the product library has none."""
+    cmd = [HIPCC, *HIP_FLAGS, "-DSPDL_PHASE_CLOCKS", "-o", CLOCKS_LIB_PATH, *sources()]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + proc.stdout)
+    return CLOCKS_LIB_PATH
+
+
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
@@ -52,3 +67,4 @@ def build(verbose: bool = False) -> str:
 if __name__ == "__main__":
     print(build(verbose=True))
     print(build_microbench(verbose=True))
+    print(build_phase_clocks(verbose=True))

@@ -78,6 +78,52 @@ template <> struct Pack<_Float16, 8> {
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Optional clocks inside the slab kernels: where a wave's time goes.  Compiled in only with
+// -DSPDL_PHASE_CLOCKS (microbench/phase_clocks.py builds such a copy of the library and prints the
+// table); without the macro every member is empty and the kernels are what they are without it.
+// A wave adds the clocks between two laps to the phase named at the second one (the counter is
+// s_memtime, the sums live in scalar registers) and leaves its sums in a global table at the end:
+// eight numbers per wave, the seven phases and the total.  A lap is also a scheduling barrier,
+// so a measured kernel is a little slower than the real one.
+enum Phase { kPhaseSetup = 0, kPhaseIssue, kPhaseScan, kPhaseSteps, kPhaseWait, kPhaseBarrier, kPhaseRest, kPhases };
+#ifdef SPDL_PHASE_CLOCKS
+constexpr int kPhaseTableWaves = 8192;
+__device__ unsigned long long spdl_phase_table[kPhaseTableWaves * 8];
+struct PhaseClocks {
+  unsigned long long first, last, acc[kPhases];
+  static __device__ __forceinline__ unsigned long long now() {
+    __builtin_amdgcn_sched_barrier(0);
+    const unsigned long long t = __builtin_readcyclecounter();
+    __builtin_amdgcn_sched_barrier(0);
+    return t;
+  }
+  __device__ __forceinline__ void start() {
+#pragma unroll
+    for (int i = 0; i < kPhases; ++i) acc[i] = 0;
+    first = last = now();
+  }
+  __device__ __forceinline__ void lap(int phase) {
+    const unsigned long long t = now();
+    acc[phase] += t - last;
+    last = t;
+  }
+  __device__ __forceinline__ void store(int wave_slot) {
+    if (wave_slot < kPhaseTableWaves && (threadIdx.x & 63) == 0) {
+      unsigned long long* d = spdl_phase_table + (size_t)wave_slot * 8;
+#pragma unroll
+      for (int i = 0; i < kPhases; ++i) d[i] = acc[i];
+      d[kPhases] = last - first;
+    }
+  }
+};
+#else
+struct PhaseClocks {
+  __device__ __forceinline__ void start() {}
+  __device__ __forceinline__ void lap(int) {}
+  __device__ __forceinline__ void store(int) {}
+};
+#endif
+
 // Maximum of two wave-uniform values on the scalar unit (left to itself the compiler moves such
 // a maximum to the vector unit as soon as one of its uses is a vector select).
 __device__ __forceinline__ int scalar_max(int a, int b) {

@@ -116,6 +116,8 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
   constexpr int WIN = 16 * NCHD;                // nonzeros per round
   constexpr int kCopies = S * 2 / 4 / 16;       // 1 KB direct-to-LDS loads per wave per slab
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+  PhaseClocks clocks;
+  clocks.start();
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -358,6 +360,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
     transpose_slab_nt();
     __syncthreads();
   }
+  clocks.lap(kPhaseSetup);
 
   for (int s = 0; s < nslabs; ++s) {
     const int slab_start = k0 + s * S;
@@ -383,10 +386,12 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
           if (ACCUM) asm volatile("" :: "v"(pv[j][i]));
         }
       store_pending();
+      clocks.lap(kPhaseRest);
       if (first && s + 1 < nslabs) {
         if constexpr (NT) fetch_slab_nt(s + 1);       // the staging area was emptied before this stage
         else copy_stage(s + 1);
       }
+      clocks.lap(kPhaseIssue);
       first = false;
       more = false;
       // First the look-ahead of every row is counted and replaced by the next one, so that all
@@ -435,6 +440,7 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
         }
         fetch(j, p[j]);
       }
+      clocks.lap(kPhaseScan);
 #pragma unroll
       for (int j = 0; j < RPG; ++j) {
         if (j == 0) __builtin_amdgcn_s_setprio(2);
@@ -489,10 +495,13 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
         }
       }
       __builtin_amdgcn_s_setprio(0);
+      clocks.lap(kPhaseSteps);
       if (more) __builtin_amdgcn_s_waitcnt(0);       // a row has more than 16*NCHD nonzeros in this slab
     } while (more);
     __builtin_amdgcn_s_waitcnt(0);
+    clocks.lap(kPhaseWait);
     __syncthreads();
+    clocks.lap(kPhaseBarrier);
     if constexpr (NT) {
       if (s + 1 < nslabs) {                           // the slab is done with, the next one has arrived
         transpose_slab_nt();
@@ -501,6 +510,8 @@ __global__ __launch_bounds__(kSdThreads) void sddmm_lane_kernel(
     }
   }
   store_pending();
+  clocks.lap(kPhaseRest);
+  clocks.store(blockIdx.x * (kSdThreads / 64) + wave);
 
   // A range whose cursor did not stop exactly at its end was not ascending: redo it directly.
 #pragma unroll

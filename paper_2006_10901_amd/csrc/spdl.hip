@@ -1020,3 +1020,10 @@ const char* spdl_status_string(int status) {
 int spdl_version(void) { return 130; }
 
 }  // extern "C"
+
+#ifdef SPDL_PHASE_CLOCKS
+// Diagnostic build only (microbench/phase_clocks.py): the table the instrumented kernels leave.
+extern "C" int spdl_debug_phase_clocks(unsigned long long* host, size_t count) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(spdl::spdl_phase_table), count * sizeof(unsigned long long));
+}
+#endif

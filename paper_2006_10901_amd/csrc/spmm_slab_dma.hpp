@@ -38,6 +38,8 @@ __global__ __launch_bounds__(64 * NW) void spmm_slab_dma_kernel(
   constexpr int kZeroOff = S * kSlabTile * 4;
   constexpr int kCopies = S / (4 * NW);                   // 1 KB direct-to-LDS loads per wave per slab
 
+  PhaseClocks clocks;
+  clocks.start();
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
@@ -173,9 +175,11 @@ __global__ __launch_bounds__(64 * NW) void spmm_slab_dma_kernel(
     const bool more = cmax[NCH - 1] == 16;
     // the next pairs, first needed in the next stage (or in the next long round of this one)
     fetch_pairs(j, (restart && !more) ? rows[j].p_begin : rows[j].p);
+    clocks.lap(kPhaseScan);
 #pragma unroll
     for (int i = 0; i < NCH; ++i)
       if (cmax[i] > 0) slab_steps(acc[j], av[i], off[i], buf, lane_b, cmax[i]);
+    clocks.lap(kPhaseSteps);
     return more;
   };
 
@@ -184,6 +188,7 @@ __global__ __launch_bounds__(64 * NW) void spmm_slab_dma_kernel(
   for (int j = 0; j < RPG; ++j) fetch_pairs(j, rows[j].p_begin);
   wait_everything();
   __builtin_amdgcn_s_barrier();
+  clocks.lap(kPhaseSetup);
   int q = 0;
   for (int tile = tile_begin; tile < tile_end; ++tile) {
     const int col = tile * kSlabTile + l16 * 4;
@@ -198,7 +203,9 @@ __global__ __launch_bounds__(64 * NW) void spmm_slab_dma_kernel(
       // its wait for the pair loads here, where they completed long ago (full wait at the end
       // of the previous stage), instead of after the copies, where it would wait for those too.
       asm volatile("v_mov_b32 %0, %0" : "+v"(aa[RPG - 1][NCH - 1]));
+      clocks.lap(kPhaseRest);
       if (q + 1 < stages) copy_stage(q + 1);
+      clocks.lap(kPhaseIssue);
       const char* buf = lds_raw + (q & 1) * kBufBytes;
 #pragma unroll
       for (int j = 0; j < RPG; ++j) {
@@ -209,7 +216,9 @@ __global__ __launch_bounds__(64 * NW) void spmm_slab_dma_kernel(
           while (long_round(j, buf, s * S, restart)) {}          // more than 16*NCH pairs in this slab
       }
       wait_everything();
+      clocks.lap(kPhaseWait);
       __builtin_amdgcn_s_barrier();
+      clocks.lap(kPhaseBarrier);
     }
 #pragma unroll
     for (int j = 0; j < RPG; ++j) {
@@ -230,6 +239,8 @@ __global__ __launch_bounds__(64 * NW) void spmm_slab_dma_kernel(
       }
     }
   }
+  clocks.lap(kPhaseRest);
+  clocks.store(blockIdx.x * NW + wave);
 }
 
 }  // namespace spdl
