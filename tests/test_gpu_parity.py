@@ -425,7 +425,7 @@ def test_forced_sddmm_variants_fp16_and_long_rows(g, oracle_lib, force):
 
 @pytest.mark.parametrize("n", [36, 64, 100, 128])
 def test_window_kernels_on_banded_masks(g, oracle_lib, force, n):
-    """The window kernels (one window of 256 rows of the dense operand in LDS per 16 sparse rows,
+    """The window kernels (one window of 256 rows of the dense operand in LDS per 8 or 16 sparse rows,
     gathers for the rest) on masks with a band: a row count that is not a multiple of 16, fewer
     columns than a window holds, a band that is not on the diagonal of a rectangular matrix, a
     uniform mask, for which no window is placed, and a causal mask (band to the left of the diagonal).  SDDMM gives the bits of the nonzero-split kernel."""
