@@ -83,12 +83,13 @@ __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirs
 // table); without the macro every member is empty and the kernels are what they are without it.
 // A wave adds the clocks between two laps to the phase named at the second one (the counter is
 // s_memtime, the sums live in scalar registers) and leaves its sums in a global table at the end:
-// eight numbers per wave, the seven phases and the total.  A lap is also a scheduling barrier,
+// ten numbers per wave: the eight phases, the total, one spare.  A lap is also a scheduling barrier,
 // so a measured kernel is a little slower than the real one.
-enum Phase { kPhaseSetup = 0, kPhaseIssue, kPhaseScan, kPhaseSteps, kPhaseWait, kPhaseBarrier, kPhaseRest, kPhases };
+enum Phase { kPhaseSetup = 0, kPhaseIssue, kPhaseScan, kPhaseSteps, kPhaseWait, kPhaseBarrier, kPhaseRest, kPhaseGather, kPhases };
+constexpr int kPhaseStride = 10;
 #ifdef SPDL_PHASE_CLOCKS
 constexpr int kPhaseTableWaves = 8192;
-__device__ unsigned long long spdl_phase_table[kPhaseTableWaves * 8];
+__device__ unsigned long long spdl_phase_table[kPhaseTableWaves * kPhaseStride];
 struct PhaseClocks {
   unsigned long long first, last, acc[kPhases];
   static __device__ __forceinline__ unsigned long long now() {
@@ -109,7 +110,7 @@ struct PhaseClocks {
   }
   __device__ __forceinline__ void store(int wave_slot) {
     if (wave_slot < kPhaseTableWaves && (threadIdx.x & 63) == 0) {
-      unsigned long long* d = spdl_phase_table + (size_t)wave_slot * 8;
+      unsigned long long* d = spdl_phase_table + (size_t)wave_slot * kPhaseStride;
 #pragma unroll
       for (int i = 0; i < kPhases; ++i) d[i] = acc[i];
       d[kPhases] = last - first;

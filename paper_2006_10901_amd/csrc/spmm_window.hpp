@@ -88,6 +88,8 @@ __global__ __launch_bounds__(64 * NW) void spmm_window_kernel(
   static_assert(W % (4 * NW) == 0, "every wave copies the same number of 4-row pieces");
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
 
+  PhaseClocks clocks;
+  clocks.start();
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
@@ -146,8 +148,11 @@ __global__ __launch_bounds__(64 * NW) void spmm_window_kernel(
   for (int t = 0; t < 4; ++t) g0[t] = g1[t] = g2[t] = g3[t] = f32x4{0.f, 0.f, 0.f, 0.f};
   const char* gbase = reinterpret_cast<const char*>(B + (col_ok ? col : 0));
 
+  clocks.lap(kPhaseSetup);
   __builtin_amdgcn_s_waitcnt(0);      // the window copy and the first chunk
+  clocks.lap(kPhaseWait);
   __syncthreads();
+  clocks.lap(kPhaseBarrier);
 
   for (int at = p_begin; __any(at < p_end); at += 64) {
     fetch(at + 64, cn, an);
@@ -157,6 +162,7 @@ __global__ __launch_bounds__(64 * NW) void spmm_window_kernel(
     const bool outw = valid && !inwin;
     const unsigned long long m_in = __builtin_amdgcn_ballot_w64(inwin);
     const unsigned long long m_out = __builtin_amdgcn_ballot_w64(outw);
+    clocks.lap(kPhaseScan);
     if (m_in != 0) {
       // positions 0 .. cmax-1 of the chunk hold every pair inside the window, in any group
       const unsigned lo = (unsigned)m_in, hi = (unsigned)(m_in >> 32);
@@ -166,6 +172,7 @@ __global__ __launch_bounds__(64 * NW) void spmm_window_kernel(
       const int off = inwin ? (int)(rel * (kWinTile * 4)) : kZeroOff;
       slab_steps(acc, av, off, lds_raw, lane_b, cmax);
     }
+    clocks.lap(kPhaseSteps);
     if (m_out != 0) {
       const float av = outw ? aa : 0.f;
       // byte offset of the pair's row of B; the sign bit marks "no gather for this pair"
@@ -193,6 +200,7 @@ __global__ __launch_bounds__(64 * NW) void spmm_window_kernel(
       if (any16 & 0x0f00u) slab_fma16_q2(acc, av, g2);
       if (any16 & 0xf000u) slab_fma16_q3(acc, av, g3);
     }
+    clocks.lap(kPhaseGather);
     cc = cn;
     aa = an;
   }
@@ -206,6 +214,8 @@ __global__ __launch_bounds__(64 * NW) void spmm_window_kernel(
     spmm_epilogue<float, 4>(acc, bias, row, relu);
     Pack<float, 4>::store(C + (size_t)row * n + col, acc);
   }
+  clocks.lap(kPhaseRest);
+  clocks.store((blockIdx.y * gridDim.x + blockIdx.x) * NW + wave);
 }
 
 }  // namespace spdl
