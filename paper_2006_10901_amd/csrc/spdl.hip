@@ -231,22 +231,29 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
     // of at most 32 columns use half of a slab tile's lanes or less.  8192 x 8192 at 5 % density:
     // slab 58 us against 26 for gathers at n = 32, 56 against 45 at n = 64; at 10 % the slab kernel
     // wins at n = 64, 66 us against 82, and still loses at n = 32, 68 against 46.)
-    const double min_reuse = n <= 32 ? 12.0 : n <= 64 ? 5.0 : 2.0;
+    // (Wide outputs that leave half the compute units without a full-size workgroup run the slab kernel
+    // with workgroups of 8 waves and twice as many stages: 4096 x 4096 at 6 % density, n = 128: 31 us
+    // against 24 for the window kernel's gathers; at 12 % 39 against 42.)
+    const double min_reuse = n <= 32 ? 12.0 : (n <= 64 || out_tiles < kComputeUnits) ? 5.0 : 2.0;
     variant = (sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) && reuse >= min_reuse && out_tiles >= kComputeUnits / 2)
                   ? kSpmmSlabDma : kSpmmRowsplit;
-    // One 64-column tile, thousands of rows of a few hundred entries, at most 1/8 dense, and not
-    // enough output tiles for the slab kernel: the shape of an attention head (paper Sec.
-    // "Application: Sparse Transformer").  The host cannot see whether the entries form a band;
-    // where the choice is between gathering and the window kernel the latter loses nothing without
-    // a band (its gathers are the row-splitting kernel's: 40.7 us against 44.6 on a uniform
-    // 8192 x 8192 mask at 5 %) and is 1.2 .. 1.3 times faster with one.  Narrower outputs leave its
-    // lanes idle and fewer rows leave it too few waves.  Where the slab kernel applies it stays the
-    // choice from the shape alone: on uniform masks it is up to 1.9 times faster than the window
-    // kernel (16384 x 4096 at 10 %), on banded ones 2.2 .. 2.6 times slower, and only the caller
-    // knows which it is (spdl_spmm_banded).
+    // Thousands of rows of a few hundred entries or more, one or two 64-column tiles, and a shape the
+    // slab kernel does not take: the shape of an attention head (paper Sec. "Application: Sparse
+    // Transformer").  The host cannot see whether the entries form a band; where the choice is
+    // between the row-splitting kernel and the window kernel the latter is 1.2 .. 1.3 times faster
+    // with a band and loses nothing without one, where no window is placed and every entry is
+    // gathered: with the four lane groups of a wave on one row and sixteen gathers in flight per
+    // round it is 5 .. 20 % faster than row-splitting on uniform masks of 2048 .. 8192 rows at 3 ..
+    // 30 % density (e.g. 4096 x 8192 at 20 %, n = 64: 71 us against 84; the LSTM matrix at 98 %
+    // sparsity, n = 128: 52 against 59).  Narrower outputs leave its lanes idle, shorter rows and fewer
+    // rows leave it too few waves in flight (rows of 60: up to 20 % slower).  Where the slab kernel
+    // applies it stays the choice from the shape alone: on uniform masks it is up to 1.9 times faster
+    // than the window kernel (16384 x 4096 at 10 %), on banded ones 2.2 .. 2.6 times slower, and only
+    // the caller knows which it is (spdl_spmm_banded).
     if (variant == kSpmmRowsplit && sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) &&
-        (int64_t)k * n < ((int64_t)1 << 29) && n > 32 && n <= kWinTile && m >= 4096 &&
-        (double)nnz >= 192.0 * (double)m && (double)nnz <= 0.125 * (double)m * (double)k)
+        (int64_t)k * n < ((int64_t)1 << 29) && n > 32 && n <= 2 * kWinTile &&
+        ((m >= 4096 && (double)nnz >= 100.0 * (double)m) ||
+         (m >= 2048 && (double)nnz >= (n > kWinTile ? 192.0 : 400.0) * (double)m)))
       variant = kSpmmWindow;
     // the caller says that the entries form a band (a problem the window kernel cannot take keeps
     // the choice made above)
@@ -527,13 +534,13 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
       // rows, also 10 % dense, takes 36 us against 24)
       const bool slab = fp32_fast && reuse >= 2.0 && (n >= 128 || reuse >= 8.0 || (reuse >= 5.0 && m >= 8192));
       variant = lane ? kSddmmLane : slab ? kSddmmSlabDma : kSddmmGroup;
-      // The shape of an attention head (33..64 columns, thousands of rows of a few hundred entries,
-      // at most 1/8 dense; paper Sec. "Application: Sparse Transformer"): the window kernel, which is
-      // the nonzero-split kernel with the rows of R around a band taken from LDS (13 % faster on a
-      // band of 256 at sequence 4096, 2 .. 10 % on uniform masks of that shape).
+      // The shape of an attention head (33..64 columns, thousands of rows of a hundred entries or
+      // more; paper Sec. "Application: Sparse Transformer"): the window kernel, which is the
+      // nonzero-split kernel with the rows of R around a band taken from LDS and the four lane groups
+      // of a wave on one row (13 % faster on a band of 256 at sequence 4096, 5 .. 20 % on uniform masks
+      // of 4096 and 8192 rows with 120 .. 500 entries per row).
       if (variant == kSddmmGroup && fp32_fast && n > 32 && n <= kWinTile && m >= 4096 && aligned(L, 16) &&
-          aligned(R, 16) && (int64_t)k * n < ((int64_t)1 << 29) && (double)nnz >= 192.0 * (double)m &&
-          (double)nnz <= 0.125 * (double)m * (double)k)
+          aligned(R, 16) && (int64_t)k * n < ((int64_t)1 << 29) && (double)nnz >= 100.0 * (double)m)
         variant = kSddmmWindow;
     } else {
       // Longer dot products: three candidates, chosen by an estimate of their run times from measured

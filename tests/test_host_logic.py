@@ -124,8 +124,11 @@ def test_validate_csr_host(spdl):
 
 
 def test_selection_uses_widest_aligned_vector(spdl):
-    s = spdl.spdl_select_spmm(8192, 10240, 128, 1 << 20, 4, 0, 0)          # 98.75 % sparse: row splitting
+    s = spdl.spdl_select_spmm(8192, 10240, 128, 1 << 19, 4, 0, 0)          # 99.4 % sparse, rows of 64: row splitting
+    assert spdl.spdl_variant_name(0, s["variant"]) == "rowsplit"
     assert s["vec"] == 4 and s["lanes_per_row"] * s["vec"] >= 128
+    s = spdl.spdl_select_spmm(8192, 10240, 128, 1 << 20, 4, 0, 0)          # 98.75 % sparse, rows of 128: gathers, four groups per row
+    assert spdl.spdl_variant_name(0, s["variant"]) == "window" and s["vec"] == 4 and s["grid_y"] == 2
     s = spdl.spdl_select_spmm(8192, 10240, 128, 8 << 20, 4, 0, 0)          # 90 % sparse: LDS slabs
     assert spdl.spdl_variant_name(0, s["variant"]) == "slabdma" and s["grid_x"] == 256
     assert spdl.spdl_select_spmm(64, 64, 130, 100, 4, 0, 0)["vec"] == 2
@@ -176,9 +179,10 @@ def test_sddmm_selection_for_long_dot_products(spdl):
 
 
 def test_spmm_selection_of_the_window_kernel(spdl):
-    """One 64-column tile, a few hundred entries per row, at most 1/8 dense, thousands of rows: the
-    shape of an attention head (paper Sec. "Application: Sparse Transformer") goes to the window
-    kernel; anything narrower, wider, denser, shorter or in half precision does not."""
+    """One or two 64-column tiles, a few hundred entries per row or more, thousands of rows, and a
+    shape the slab kernel does not take: the shape of an attention head (paper Sec. "Application:
+    Sparse Transformer") goes to the window kernel; anything narrower, wider, with shorter or fewer
+    rows, in half precision, or dense enough for the slab kernel does not."""
     def chosen(m, k, n, nnz, eb=4):
         return spdl.spdl_variant_name(0, spdl.spdl_select_spmm(m, k, n, nnz, eb, 0, 0)["variant"])
     assert chosen(4096, 4096, 64, 1678008) == "window"            # config 4
@@ -190,9 +194,19 @@ def test_spmm_selection_of_the_window_kernel(spdl):
     assert chosen(8192, 8192, 32, int(8192 * 8192 * 0.05)) == "rowsplit"     # narrow output: gathers
     assert chosen(8192, 8192, 32, int(8192 * 8192 * 0.3)) == "slabdma"
     assert chosen(4096, 4096, 32, 1678008) == "rowsplit"
-    assert chosen(4096, 4096, 128, 1678008) != "window"
-    assert chosen(2048, 2048, 64, 2048 * 400) == "rowsplit"
-    assert chosen(4096, 4096, 64, 4096 * 100) == "rowsplit"       # short rows
+    assert chosen(4096, 4096, 128, 1678008) == "slabdma"          # 10 % dense: slabs, in workgroups of 8 waves
+    assert chosen(4096, 4096, 128, int(4096 * 4096 * 0.06)) == "window"     # ... too sparse for those
+    assert chosen(8192, 4096, 128, int(8192 * 4096 * 0.06)) == "slabdma"    # full-size workgroups take it
+    assert chosen(8192, 10240, 128, 1677910) == "window"          # the LSTM matrix at 98 % sparsity
+    assert chosen(8192, 10240, 128, 4195643) == "slabdma"         # ... at 95 %
+    assert chosen(2048, 4096, 128, 2048 * 400) == "window"
+    assert chosen(1024, 4096, 128, 1024 * 400) == "rowsplit"      # too few rows
+    assert chosen(4096, 4096, 256, 4096 * 246) == "slabdma"       # wider than two tiles: never the window kernel
+    assert chosen(4096, 65536, 256, 4096 * 246) == "rowsplit"
+    assert chosen(4096, 4096, 64, int(4096 * 4096 * 0.3)) == "window"       # denser, still no slab shape: gathers
+    assert chosen(2048, 2048, 64, 2048 * 300) == "rowsplit"       # few rows and not long enough
+    assert chosen(2048, 2048, 64, 2048 * 400) == "window"
+    assert chosen(4096, 4096, 64, 4096 * 60) == "rowsplit"        # short rows
     assert chosen(8192, 8192, 64, int(8192 * 8192 * 0.3)) == "slabdma"
     assert chosen(4096, 4096, 64, 1678008, eb=2) != "window"
     try:
@@ -214,7 +228,7 @@ def test_sddmm_selection_of_the_window_kernel(spdl):
     assert chosen(4096, 4096, 32, 1678008) == "group"
     assert chosen(4096, 4096, 128, 1678008) == "lane"
     assert chosen(2048, 8192, 64, 2048 * 400) == "group"           # too few rows
-    assert chosen(4096, 4096, 64, 4096 * 100) == "group"          # short rows
+    assert chosen(4096, 4096, 64, 4096 * 60) == "group"           # short rows
     assert chosen(4096, 4096, 64, 1678008, eb=2) != "window"
     # uniform masks of that density with enough rows for full slab panels: the slab kernel
     assert chosen(8192, 2048, 64, int(8192 * 2048 * 0.1)) == "slabdma"
