@@ -246,14 +246,22 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
     // round it is 5 .. 20 % faster than row-splitting on uniform masks of 2048 .. 8192 rows at 3 ..
     // 30 % density (e.g. 4096 x 8192 at 20 %, n = 64: 71 us against 84; the LSTM matrix at 98 %
     // sparsity, n = 128: 52 against 59).  Narrower outputs leave its lanes idle, shorter rows and fewer
-    // rows leave it too few waves in flight (rows of 60: up to 20 % slower).  Where the slab kernel
+    // rows leave it too few waves in flight (rows of 60: up to 20 % slower).  A wave owns a whole
+    // row, though, and on strongly skewed row lengths (log-normal, a few rows of thousands of
+    // entries among rows of hundreds) that costs it up to 1.6 times the row-splitting kernel's time
+    // at n <= 64, where that kernel copes (4096 x 4096 at 6 %: 67 us against 40), while at n = 128
+    // row-splitting is the one that collapses (8192 x 4096 at 3 %: 163 us against 87).  One tile: only
+    // the attention-head shape proper (thousands of rows of 200 entries or more, at most 1/8 dense);
+    // two tiles: from 100 entries per row on (192 below 4096 rows).  Where the slab kernel
     // applies it stays the choice from the shape alone: on uniform masks it is up to 1.9 times faster
     // than the window kernel (16384 x 4096 at 10 %), on banded ones 2.2 .. 2.6 times slower, and only
     // the caller knows which it is (spdl_spmm_banded).
     if (variant == kSpmmRowsplit && sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) &&
-        (int64_t)k * n < ((int64_t)1 << 29) && n > 32 && n <= 2 * kWinTile &&
-        ((m >= 4096 && (double)nnz >= 100.0 * (double)m) ||
-         (m >= 2048 && (double)nnz >= (n > kWinTile ? 192.0 : 400.0) * (double)m)))
+        (int64_t)k * n < ((int64_t)1 << 29) &&
+        ((n > 32 && n <= kWinTile && m >= 4096 && (double)nnz >= 192.0 * (double)m &&
+          (double)nnz <= 0.125 * (double)m * (double)k) ||
+         (n > kWinTile && n <= 2 * kWinTile &&
+          ((m >= 4096 && (double)nnz >= 100.0 * (double)m) || (m >= 2048 && (double)nnz >= 192.0 * (double)m)))))
       variant = kSpmmWindow;
     // the caller says that the entries form a band (a problem the window kernel cannot take keeps
     // the choice made above)
@@ -534,13 +542,17 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
       // rows, also 10 % dense, takes 36 us against 24)
       const bool slab = fp32_fast && reuse >= 2.0 && (n >= 128 || reuse >= 8.0 || (reuse >= 5.0 && m >= 8192));
       variant = lane ? kSddmmLane : slab ? kSddmmSlabDma : kSddmmGroup;
-      // The shape of an attention head (33..64 columns, thousands of rows of a hundred entries or
-      // more; paper Sec. "Application: Sparse Transformer"): the window kernel, which is the
-      // nonzero-split kernel with the rows of R around a band taken from LDS and the four lane groups
-      // of a wave on one row (13 % faster on a band of 256 at sequence 4096, 5 .. 20 % on uniform masks
-      // of 4096 and 8192 rows with 120 .. 500 entries per row).
+      // The shape of an attention head (33..64 columns, thousands of rows of a few hundred entries,
+      // at most 1/8 dense; paper Sec. "Application: Sparse Transformer"): the window kernel, which is
+      // the nonzero-split kernel with the rows of R around a band taken from LDS and the four lane
+      // groups of a wave on one row (13 % faster on a band of 256 at sequence 4096, 5 .. 20 % on uniform
+      // masks of that shape).  Not wider than that: the nonzero-split kernel does not care how long
+      // the rows are, the window kernel owns rows, and on log-normal row lengths it takes 1.5 times as
+      // long (4096 x 4096 at 6 %: 26 us against 17) although the waves of a workgroup share what a row
+      // holds beyond 512 entries.
       if (variant == kSddmmGroup && fp32_fast && n > 32 && n <= kWinTile && m >= 4096 && aligned(L, 16) &&
-          aligned(R, 16) && (int64_t)k * n < ((int64_t)1 << 29) && (double)nnz >= 100.0 * (double)m)
+          aligned(R, 16) && (int64_t)k * n < ((int64_t)1 << 29) && (double)nnz >= 192.0 * (double)m &&
+          (double)nnz <= 0.125 * (double)m * (double)k)
         variant = kSddmmWindow;
     } else {
       // Longer dot products: three candidates, chosen by an estimate of their run times from measured

@@ -503,6 +503,37 @@ def _with_dense_rows(A, rows, seed):
     return wl.Csr(A.m, A.k, ro.astype(np.int32), ci, rng.standard_normal(int(ro[-1])).astype(np.float32))
 
 
+@pytest.mark.parametrize("n", [64, 100])
+def test_sddmm_window_kernel_shares_the_tail_of_long_rows(g, oracle_lib, force, n):
+    """The SDDMM window kernel gives a wave the first 512 entries of its row; what a longer row
+    holds beyond them is dealt to all waves of the workgroup.  A banded mask in which some rows hold
+    every column (first, last, two neighbours in one workgroup, one in a ragged last workgroup) and
+    one holds exactly 512 and one 513 entries, against the oracle and bit for bit against the
+    nonzero-split kernel."""
+    import paper_2006_10901_amd as spdl
+    base = wl.banded_attention_csr(1003, 64, 0.12, 4100 + n)
+    A = _with_dense_rows(base, {0, 17, 18, 500, 1002}, 4101 + n)
+    lens = np.diff(A.row_offsets).astype(np.int64)
+    for r, want in ((40, 512), (41, 513)):
+        lens[r] = want
+    ro = np.zeros(A.m + 1, dtype=np.int64)
+    np.cumsum(lens, out=ro[1:])
+    ci = np.empty(ro[-1], dtype=np.int32)
+    for i in range(A.m):
+        old = A.column_indices[A.row_offsets[i]:A.row_offsets[i + 1]]
+        ci[ro[i]:ro[i + 1]] = old if lens[i] == len(old) else np.arange(lens[i])
+    A = wl.Csr(A.m, A.k, ro.astype(np.int32), ci, np.ones(int(ro[-1]), np.float32))
+    L, R = wl.dense(A.m, n, 4102 + n), wl.dense(A.k, n, 4103 + n)
+    ref, S = oracle_lib.sddmm(A.m, A.k, n, A.row_offsets, A.column_indices, L, R)
+    names = {spdl.spdl_variant_name(1, v): v for v in sddmm_variants()}
+    force(1, names["window"])
+    assert spdl.spdl_variant_name(1, spdl.spdl_select_sddmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"]) == "window"
+    got = g.gpu_sddmm(A, L, R, n)
+    g.assert_close(got, ref, S, g.TOL_F32, f"window sddmm, long rows, n={n}")
+    force(1, names["group"])
+    assert np.array_equal(got, g.gpu_sddmm(A, L, R, n))
+
+
 def test_spmm_wide_outputs_tile_inner_slab_kernel(g, oracle_lib, force):
     """Outputs wide enough for two rows per lane group and several tiles per workgroup: the slab
     kernel that scans a slab once for all its tiles.  A ragged last tile, a density at the edge of

@@ -203,10 +203,9 @@ def test_spmm_selection_of_the_window_kernel(spdl):
     assert chosen(1024, 4096, 128, 1024 * 400) == "rowsplit"      # too few rows
     assert chosen(4096, 4096, 256, 4096 * 246) == "slabdma"       # wider than two tiles: never the window kernel
     assert chosen(4096, 65536, 256, 4096 * 246) == "rowsplit"
-    assert chosen(4096, 4096, 64, int(4096 * 4096 * 0.3)) == "window"       # denser, still no slab shape: gathers
-    assert chosen(2048, 2048, 64, 2048 * 300) == "rowsplit"       # few rows and not long enough
-    assert chosen(2048, 2048, 64, 2048 * 400) == "window"
-    assert chosen(4096, 4096, 64, 4096 * 60) == "rowsplit"        # short rows
+    assert chosen(4096, 4096, 64, int(4096 * 4096 * 0.3)) == "rowsplit"     # one tile: the attention-head shape only
+    assert chosen(2048, 2048, 64, 2048 * 400) == "rowsplit"
+    assert chosen(4096, 4096, 64, 4096 * 100) == "rowsplit"       # short rows
     assert chosen(8192, 8192, 64, int(8192 * 8192 * 0.3)) == "slabdma"
     assert chosen(4096, 4096, 64, 1678008, eb=2) != "window"
     try:
@@ -228,7 +227,7 @@ def test_sddmm_selection_of_the_window_kernel(spdl):
     assert chosen(4096, 4096, 32, 1678008) == "group"
     assert chosen(4096, 4096, 128, 1678008) == "lane"
     assert chosen(2048, 8192, 64, 2048 * 400) == "group"           # too few rows
-    assert chosen(4096, 4096, 64, 4096 * 60) == "group"           # short rows
+    assert chosen(4096, 4096, 64, 4096 * 100) == "group"          # short rows
     assert chosen(4096, 4096, 64, 1678008, eb=2) != "window"
     # uniform masks of that density with enough rows for full slab panels: the slab kernel
     assert chosen(8192, 2048, 64, int(8192 * 2048 * 0.1)) == "slabdma"
