@@ -18,7 +18,7 @@
 
 namespace spdl {
 
-constexpr int kWinOwn = 512;     // entries of its own row that a wave walks alone (a multiple of 64)
+constexpr int kWinOwn = 512;     // entries of its own row that a wave walks alone, at least (a multiple of 64)
 
 template <int NW, int NC>
 __global__ __launch_bounds__(64 * NW, 4) void sddmm_window_kernel(
@@ -47,6 +47,11 @@ __global__ __launch_bounds__(64 * NW, 4) void sddmm_window_kernel(
 
   const int r0 = blockIdx.x * NW;
   const int r1 = min(m, r0 + NW) - 1;
+  // the offsets of all rows of the workgroup (for the rows that are shared at the end), requested
+  // with everything else of the set-up and moved to scalar registers once they have arrived
+  int ro_raw[NW + 1];
+#pragma unroll
+  for (int i = 0; i <= NW; ++i) ro_raw[i] = row_offsets[min(r0 + i, m)];
   const int c0 = win_place<W>(row_offsets, column_indices, r0, r1, k);
 
   // The window copy, chunk after chunk: copy i of wave w fills window rows (i*NW + w)*4 .. +3 (256
@@ -134,19 +139,27 @@ __global__ __launch_bounds__(64 * NW, 4) void sddmm_window_kernel(
   load_l(Lown);
   __builtin_amdgcn_s_waitcnt(0);      // the window copy
   __syncthreads();
+  int ro_all[NW + 1];
+#pragma unroll
+  for (int i = 0; i <= NW; ++i) ro_all[i] = uniform(ro_raw[i]);
 
   // Every wave walks the first kWinOwn entries of its own row.  What a longer row holds beyond them
   // is dealt to all waves of the workgroup, 64 entries at a time (every entry's result is its own,
   // so nothing has to be added up): a row of thousands of entries among rows of hundreds would
   // otherwise keep one wave busy long after the others are done (a matrix with log-normal row
   // lengths, 4096 x 4096 at 6 %, n = 64: 60 us against 17 for the nonzero-split kernel).
-  walk(p_begin, min(p_end, p_begin + kWinOwn), 64, p_end, Lown);
-  for (int i = 0; i < NW && r0 + i < m; ++i) {
-    const int rb = uniform(row_offsets[r0 + i]), re = uniform(row_offsets[r0 + i + 1]);
-    if (re - rb <= kWinOwn) continue;
+  // The share a wave walks alone grows with the mean row length of the matrix (9/8 of it, rounded
+  // up to whole rounds), so rows that are long but alike are not shared at all.
+  const int mean = nnz / m;
+  const int own = max(kWinOwn, (mean + (mean >> 3) + 63) & ~63);
+  walk(p_begin, min(p_end, p_begin + own), 64, p_end, Lown);
+#pragma unroll
+  for (int i = 0; i < NW; ++i) {
+    const int rb = ro_all[i], re = ro_all[i + 1];        // (rows past m: empty)
+    if (re - rb <= own) continue;
     const float* Lrow = L + (size_t)(r0 + i) * n;
     load_l(Lrow);
-    walk(rb + kWinOwn + 64 * wave, re, 64 * NW, re, Lrow);
+    walk(rb + own + 64 * wave, re, 64 * NW, re, Lrow);
   }
 }
 

@@ -235,7 +235,13 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
     // with workgroups of 8 waves and twice as many stages: 4096 x 4096 at 6 % density, n = 128: 31 us
     // against 24 for the window kernel's gathers; at 12 % 39 against 42.)
     const double min_reuse = n <= 32 ? 12.0 : (n <= 64 || out_tiles < kComputeUnits) ? 5.0 : 2.0;
-    variant = (sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) && reuse >= min_reuse && out_tiles >= kComputeUnits / 2)
+    // (Dense matrices gain so much from the slab kernel that it pays with most compute units idle:
+    // 6144 x 2048 at 35 %, n = 64, 96 workgroups: 36 us against 54 for row-splitting; 4096 x 4096 at
+    // 50 %, 64 workgroups: 87 against 98; at 20 % and 35 % respectively the two are level.)
+    const int64_t min_tiles = (n > 32 && n <= 2 * kSlabTile && reuse >= 32.0)   ? kComputeUnits / 4
+                              : (n > 32 && n <= 2 * kSlabTile && reuse >= 16.0) ? 3 * kComputeUnits / 8
+                                                                                 : kComputeUnits / 2;
+    variant = (sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) && reuse >= min_reuse && out_tiles >= min_tiles)
                   ? kSpmmSlabDma : kSpmmRowsplit;
     // Thousands of rows of a few hundred entries or more, one or two 64-column tiles, and a shape the
     // slab kernel does not take: the shape of an attention head (paper Sec. "Application: Sparse
@@ -246,22 +252,19 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
     // round it is 5 .. 20 % faster than row-splitting on uniform masks of 2048 .. 8192 rows at 3 ..
     // 30 % density (e.g. 4096 x 8192 at 20 %, n = 64: 71 us against 84; the LSTM matrix at 98 %
     // sparsity, n = 128: 52 against 59).  Narrower outputs leave its lanes idle, shorter rows and fewer
-    // rows leave it too few waves in flight (rows of 60: up to 20 % slower).  A wave owns a whole
-    // row, though, and on strongly skewed row lengths (log-normal, a few rows of thousands of
-    // entries among rows of hundreds) that costs it up to 1.6 times the row-splitting kernel's time
-    // at n <= 64, where that kernel copes (4096 x 4096 at 6 %: 67 us against 40), while at n = 128
-    // row-splitting is the one that collapses (8192 x 4096 at 3 %: 163 us against 87).  One tile: only
-    // the attention-head shape proper (thousands of rows of 200 entries or more, at most 1/8 dense);
-    // two tiles: from 100 entries per row on (192 below 4096 rows).  Where the slab kernel
+    // rows leave it too few waves in flight (rows of 60: up to 20 % slower).  A wave owns a row, but
+    // what a row holds beyond 512 pairs is dealt to all waves of its workgroup, so strongly skewed
+    // row lengths (log-normal, a few rows of thousands of entries among rows of hundreds) are no
+    // reason to hold back: 4096 x 4096 at 6 %, n = 64: 27 us against 40 for row-splitting, n = 128:
+    // 46 against 82.  Where the slab kernel
     // applies it stays the choice from the shape alone: on uniform masks it is up to 1.9 times faster
     // than the window kernel (16384 x 4096 at 10 %), on banded ones 2.2 .. 2.6 times slower, and only
     // the caller knows which it is (spdl_spmm_banded).
     if (variant == kSpmmRowsplit && sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) &&
         (int64_t)k * n < ((int64_t)1 << 29) &&
-        ((n > 32 && n <= kWinTile && m >= 4096 && (double)nnz >= 192.0 * (double)m &&
-          (double)nnz <= 0.125 * (double)m * (double)k) ||
-         (n > kWinTile && n <= 2 * kWinTile &&
-          ((m >= 4096 && (double)nnz >= 100.0 * (double)m) || (m >= 2048 && (double)nnz >= 192.0 * (double)m)))))
+        n > 32 && n <= 2 * kWinTile &&
+        ((m >= 4096 && (double)nnz >= 100.0 * (double)m) ||
+         (m >= 2048 && (double)nnz >= (n > kWinTile ? 192.0 : 400.0) * (double)m)))
       variant = kSpmmWindow;
     // the caller says that the entries form a band (a problem the window kernel cannot take keeps
     // the choice made above)

@@ -24,8 +24,12 @@
 // non-finite number left over from an earlier row of B.
 //
 // Any CSR input gives the right result: nothing depends on the order of a row's entries, and
-// the window's position is only a matter of speed.  After the window is in place the waves do
-// not synchronise again.  Needs n % 4 == 0, 16-byte aligned B and C, k * n * 4 < 2^31.
+// the window's position is only a matter of speed.  A wave walks the first 512 pairs of its row
+// alone (or 9/8 of the mean row length, if that is more); what a longer row holds beyond them is dealt to all waves of the workgroup (64 pairs per
+// wave and round, gathers only), whose partial sums meet in LDS and are added by the row's owner,
+// so a few very long rows among short ones do not leave one wave working while the others have
+// finished.  Workgroups without such a row do not synchronise again once the window is in place.
+// Needs n % 4 == 0, 16-byte aligned B and C, k * n * 4 < 2^31.
 #pragma once
 #include "common.hpp"
 #include "spmm_slab.hpp"
@@ -38,8 +42,51 @@ template <int NW>
 struct WinShape {
   static constexpr int kRows = NW;                           // sparse rows per workgroup
   static constexpr int kW = 256;                             // rows of B in the window
-  static constexpr int kLdsBytes = (kW + 1) * kWinTile * 4;  // + the all-zero row
+  static constexpr int kPartialOff = (kW + 1) * kWinTile * 4; // after the window and the all-zero row:
+  static constexpr int kLdsBytes = kPartialOff + NW * kWinTile * 4;   // one row of partial sums per wave
 };
+
+constexpr int kWinOwnPairs = 512;            // entries of its own row that a wave walks alone (a multiple of 64)
+
+// The tail of a long row, shared by the waves of a workgroup: pairs begin + 16 sub .. per group,
+// + stride, ... below end, every one gathered from global memory (no window), four loads in
+// flight per group.  Returns this lane's four columns of the partial sum.  Lean on
+// purpose: the main kernel has no registers to spare, and this runs only for rows of more than
+// kWinOwnPairs entries.  A lane without a pair at a position skips the load and the multiply-add,
+// so nothing outside a row's own entries reaches its sum.
+__device__ __forceinline__ f32x4 win_tail_gather(const int* __restrict__ column_indices,
+                                                          const float* __restrict__ values, const char* gbase,
+                                                          int begin, int end, int stride, int n, int sub, int l16) {
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int at = begin + 16 * sub; __any(at < end); at += stride) {
+    const bool valid = at + l16 < end;
+    const int idx = valid ? at + l16 : begin;
+    const float a = valid ? values[idx] : 0.f;
+    const int goff = valid ? (int)((unsigned)column_indices[idx] * (unsigned)n * 4u) : (int)0x80000000;
+#define SPDL_TAIL1(T)                                                                                          \
+  const int o##T = __builtin_amdgcn_update_dpp(0, goff, 0x150 + (T), 0xf, 0xf, false);                          \
+  const float av##T = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x150 + (T), 0xf, 0xf, false)); \
+  f32x4 b##T = {0.f, 0.f, 0.f, 0.f};                                                                            \
+  if (o##T >= 0) b##T = *reinterpret_cast<const f32x4*>(gbase + (unsigned)o##T);
+#define SPDL_TAILF(T)                                                                                          \
+  if (o##T >= 0) {                                                                                              \
+    acc.x = __builtin_fmaf(av##T, b##T.x, acc.x);                                                               \
+    acc.y = __builtin_fmaf(av##T, b##T.y, acc.y);                                                               \
+    acc.z = __builtin_fmaf(av##T, b##T.z, acc.z);                                                               \
+    acc.w = __builtin_fmaf(av##T, b##T.w, acc.w);                                                               \
+  }
+#define SPDL_TAIL4(A, B, C, D)                                                                                 \
+  {                                                                                                             \
+    SPDL_TAIL1(A) SPDL_TAIL1(B) SPDL_TAIL1(C) SPDL_TAIL1(D)                                                     \
+    SPDL_TAILF(A) SPDL_TAILF(B) SPDL_TAILF(C) SPDL_TAILF(D)                                                     \
+  }
+    SPDL_TAIL4(0, 1, 2, 3) SPDL_TAIL4(4, 5, 6, 7) SPDL_TAIL4(8, 9, 10, 11) SPDL_TAIL4(12, 13, 14, 15)
+#undef SPDL_TAIL1
+#undef SPDL_TAILF
+#undef SPDL_TAIL4
+  }
+  return acc;
+}
 
 // Column of the entry at quantile j/4 of the row [b, e), e > b (a wave-uniform load).
 __device__ __forceinline__ int win_quantile(const int* __restrict__ ci, int b, int e, int j) {
@@ -77,7 +124,7 @@ __device__ __forceinline__ int win_place(const int* __restrict__ row_offsets, co
 }
 
 template <int NW>
-__global__ __launch_bounds__(64 * NW) void spmm_window_kernel(
+__global__ __launch_bounds__(64 * NW, 4) void spmm_window_kernel(
     int m, int k, int n, int nnz, const int* __restrict__ row_offsets,
     const int* __restrict__ column_indices, const float* __restrict__ values, const float* __restrict__ B,
     float* __restrict__ C, const float* __restrict__ bias, int relu) {
@@ -106,6 +153,11 @@ __global__ __launch_bounds__(64 * NW) void spmm_window_kernel(
 
   const int r0 = panel * Sh::kRows;
   const int r1 = min(m, r0 + Sh::kRows) - 1;
+  // the offsets of all rows of the workgroup (for the rows that are shared at the end), requested
+  // with everything else of the set-up and moved to scalar registers once they have arrived
+  int ro_raw[NW + 1];
+#pragma unroll
+  for (int i = 0; i <= NW; ++i) ro_raw[i] = row_offsets[min(r0 + i, m)];
   const int c0 = win_place<W>(row_offsets, column_indices, r0, r1, k);
 
   // The window copy: copy i of wave w fills window rows (i*NW + w)*4 .. +3, lane L row L/16 of
@@ -129,7 +181,7 @@ __global__ __launch_bounds__(64 * NW) void spmm_window_kernel(
   const int row = r0 + wave;
   const bool row_ok = row < m;
   const int p_begin = (row_ok ? row_offsets[row] : 0) + 16 * sub;
-  const int p_end = row_ok ? row_offsets[row + 1] : 0;
+  const int p_row_end = row_ok ? row_offsets[row + 1] : 0;
 
   auto fetch = [&](int at, int& c, float& a) {
     const unsigned o = (unsigned)min(at + l16, last_nz) << 2;
@@ -153,6 +205,15 @@ __global__ __launch_bounds__(64 * NW) void spmm_window_kernel(
   clocks.lap(kPhaseWait);
   __syncthreads();
   clocks.lap(kPhaseBarrier);
+  int ro_all[NW + 1];
+#pragma unroll
+  for (int i = 0; i <= NW; ++i) ro_all[i] = uniform(ro_raw[i]);
+  // A wave walks at most `own` pairs of its row alone (the rest of a longer row: below): 9/8 of the
+  // mean row length of the matrix, in whole rounds, so rows that are long but alike are not shared
+  // at all.
+  const int mean = nnz / m;
+  const int own = max(kWinOwnPairs, (mean + (mean >> 3) + 63) & ~63);
+  const int p_end = min(p_row_end, p_begin - 16 * sub + own);
 
   for (int at = p_begin; __any(at < p_end); at += 64) {
     fetch(at + 64, cn, an);
@@ -203,6 +264,33 @@ __global__ __launch_bounds__(64 * NW) void spmm_window_kernel(
     clocks.lap(kPhaseGather);
     cc = cn;
     aa = an;
+  }
+
+  // What a row holds beyond kWinOwnPairs pairs is dealt to all waves of the workgroup, 64 pairs at
+  // a time; their partial sums go through LDS to the wave that owns the row.  A row of thousands of
+  // entries among rows of hundreds would otherwise keep one wave busy long after the others are
+  // done.  (The loop is the same for every wave of the workgroup, so its barriers are met by all.)
+  float* partials = reinterpret_cast<float*>(lds_raw + Sh::kPartialOff);
+#pragma unroll
+  for (int i = 0; i < NW; ++i) {
+    const int rb = ro_all[i], re = ro_all[i + 1];       // (rows past m: empty)
+    if (re - rb <= own) continue;
+    f32x4 part = win_tail_gather(column_indices, values, gbase, rb + own + 64 * wave, re, 64 * NW, n, sub, l16);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      part[v] += __shfl_xor(part[v], 16, kWave);
+      part[v] += __shfl_xor(part[v], 32, kWave);
+    }
+    if (sub == 0) *reinterpret_cast<f32x4*>(partials + wave * kWinTile + l16 * 4) = part;
+    __syncthreads();
+    if (wave == i && sub == 0) {
+#pragma unroll
+      for (int w2 = 0; w2 < NW; ++w2) {
+        const f32x4 pv = *reinterpret_cast<const f32x4*>(partials + w2 * kWinTile + l16 * 4);
+        acc[0] += pv.x; acc[1] += pv.y; acc[2] += pv.z; acc[3] += pv.w;
+      }
+    }
+    __syncthreads();
   }
 
 #pragma unroll

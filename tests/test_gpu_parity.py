@@ -534,6 +534,43 @@ def test_sddmm_window_kernel_shares_the_tail_of_long_rows(g, oracle_lib, force, 
     assert np.array_equal(got, g.gpu_sddmm(A, L, R, n))
 
 
+@pytest.mark.parametrize("n", [64, 100])
+def test_spmm_window_kernel_shares_the_tail_of_long_rows(g, oracle_lib, force, n):
+    """The SpMM window kernel gives a wave the first 512 pairs of its row; what a longer row holds
+    beyond them is dealt to all waves of the workgroup, whose partial sums the owner adds.  The
+    same mask as for the SDDMM kernel (rows that hold every column: first, last, two neighbours in
+    one workgroup, one in a ragged last workgroup; one row of exactly 512 and one of 513 entries)
+    with random values, one and two column tiles, with and without the fused bias + ReLU."""
+    import torch
+    import paper_2006_10901_amd as spdl
+    base = wl.banded_attention_csr(1003, 64, 0.12, 4200 + n)
+    A = _with_dense_rows(base, {0, 17, 18, 500, 1002}, 4201 + n)
+    lens = np.diff(A.row_offsets).astype(np.int64)
+    for r, want in ((40, 512), (41, 513)):
+        lens[r] = want
+    ro = np.zeros(A.m + 1, dtype=np.int64)
+    np.cumsum(lens, out=ro[1:])
+    ci = np.empty(ro[-1], dtype=np.int32)
+    for i in range(A.m):
+        old = A.column_indices[A.row_offsets[i]:A.row_offsets[i + 1]]
+        ci[ro[i]:ro[i + 1]] = old if lens[i] == len(old) else np.arange(lens[i])
+    vals = np.random.default_rng(4202 + n).standard_normal(int(ro[-1])).astype(np.float32)
+    A = wl.Csr(A.m, A.k, ro.astype(np.int32), ci, vals)
+    B = wl.dense(A.k, n, 4203 + n)
+    names = {spdl.spdl_variant_name(0, v): v for v in spmm_variants()}
+    force(0, names["window"])
+    assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(A.m, A.k, n, A.nnz, 4, 0, 0)["variant"]) == "window"
+    C, S = oracle_lib.spmm(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, B)
+    g.assert_close(g.gpu_spmm(A, B, n, None), C, S, g.TOL_F32, f"window spmm, long rows, n={n}")
+    bias = np.random.default_rng(4204 + n).standard_normal(A.m).astype(np.float32)
+    C, S = oracle_lib.spmm_bias_relu(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, B, bias, True)
+    d = g.DevCsr(A)
+    out = torch.full((A.m, n), float("nan"), dtype=torch.float32, device="cuda")
+    spdl.spdl_spmm_bias_relu(A.m, A.k, n, A.nnz, d.ro, d.ci, d.val, None, g.dev(B), g.dev(bias), True, out)
+    torch.cuda.synchronize()
+    g.assert_close(out.cpu().numpy(), C, S, g.TOL_F32, f"window spmm + bias + relu, long rows, n={n}")
+
+
 def test_spmm_wide_outputs_tile_inner_slab_kernel(g, oracle_lib, force):
     """Outputs wide enough for two rows per lane group and several tiles per workgroup: the slab
     kernel that scans a slab once for all its tiles.  A ragged last tile, a density at the edge of

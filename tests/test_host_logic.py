@@ -203,10 +203,17 @@ def test_spmm_selection_of_the_window_kernel(spdl):
     assert chosen(1024, 4096, 128, 1024 * 400) == "rowsplit"      # too few rows
     assert chosen(4096, 4096, 256, 4096 * 246) == "slabdma"       # wider than two tiles: never the window kernel
     assert chosen(4096, 65536, 256, 4096 * 246) == "rowsplit"
-    assert chosen(4096, 4096, 64, int(4096 * 4096 * 0.3)) == "rowsplit"     # one tile: the attention-head shape only
-    assert chosen(2048, 2048, 64, 2048 * 400) == "rowsplit"
-    assert chosen(4096, 4096, 64, 4096 * 100) == "rowsplit"       # short rows
+    assert chosen(4096, 4096, 64, int(4096 * 4096 * 0.3)) == "window"       # denser, still no slab shape: gathers
+    assert chosen(2048, 2048, 64, 2048 * 300) == "rowsplit"       # few rows and not long enough
+    assert chosen(2048, 2048, 64, 2048 * 400) == "window"
+    assert chosen(4096, 4096, 64, 4096 * 60) == "rowsplit"        # short rows
     assert chosen(8192, 8192, 64, int(8192 * 8192 * 0.3)) == "slabdma"
+    # dense matrices take the slab kernel with fewer workgroups than half the compute units
+    assert chosen(6144, 2048, 64, int(6144 * 2048 * 0.35)) == "slabdma"       # 96 workgroups
+    assert chosen(6144, 2048, 64, int(6144 * 2048 * 0.2)) == "window"
+    assert chosen(4096, 4096, 64, int(4096 * 4096 * 0.5)) == "slabdma"        # 64 workgroups
+    assert chosen(3072, 3072, 128, int(3072 * 3072 * 0.35)) == "slabdma"
+    assert chosen(2048, 4096, 64, int(2048 * 4096 * 0.5)) == "window"         # 32 workgroups: too few
     assert chosen(4096, 4096, 64, 1678008, eb=2) != "window"
     try:
         spdl.spdl_force_variant(0, 4)
