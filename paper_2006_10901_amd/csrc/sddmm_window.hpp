@@ -159,7 +159,9 @@ __global__ __launch_bounds__(64 * NW, 4) void sddmm_window_kernel(
     if (re - rb <= own) continue;
     const float* Lrow = L + (size_t)(r0 + i) * n;
     load_l(Lrow);
-    walk(rb + own + 64 * wave, re, 64 * NW, re, Lrow);
+    // (the first 64 entries of row i's tail go to wave i, the next to wave i + 1, ...: short tails
+    // of several rows then do not all land on the first waves)
+    walk(rb + own + 64 * ((wave + NW - i) & (NW - 1)), re, 64 * NW, re, Lrow);
   }
 }
 
