@@ -95,13 +95,28 @@ bool slab_usable(int n, int nnz, const void* B, const void* C) {
   return n % 4 == 0 && n < (1 << 21) && nnz < (1 << 29) && aligned(B, 4 * sizeof(T)) && aligned(C, 4 * sizeof(T));
 }
 
-// One workgroup fits per CU (LDS), so a panel's tiles are split into just enough groups to
-// give every CU a workgroup; each workgroup then walks its tiles back to back.
-int slab_tiles_per_wg(int panels, int tiles) {
-  int groups = (kComputeUnits + panels - 1) / panels;
-  groups = std::max(1, std::min(groups, tiles));
-  return (tiles + groups - 1) / groups;
+// A slab kernel's workgroup fills a compute unit (LDS), so a grid of more than `slots` workgroups
+// runs in rounds.  `total` units of work per panel (tiles of C, slabs of A's columns), walked back
+// to back by one workgroup, are dealt to the number of workgroups per panel that gives the shortest
+// chain: rounds x (units per workgroup + two units' worth of set-up).  (3072 rows, 48 panels: six
+// workgroups per panel would be 288, a second round for 32 of them; five make 240 in one round.)
+// Returns the units per workgroup.
+int split_for_machine(int panels, int total, int slots = kComputeUnits) {
+  int best_units = total;
+  double best = 1e300;
+  for (int parts = 1; parts <= std::min(total, slots); ++parts) {
+    const int units = (total + parts - 1) / parts;
+    const int64_t wgs = (int64_t)panels * ((total + units - 1) / units);
+    const double cost = (double)((wgs + slots - 1) / slots) * (units + 2.0);
+    if (cost < best - 1e-9) {
+      best = cost;
+      best_units = units;
+    }
+  }
+  return best_units;
 }
+
+int slab_tiles_per_wg(int panels, int tiles, int slots = kComputeUnits) { return split_for_machine(panels, tiles, slots); }
 
 // Rows per 16-lane group of the copy-based slab kernel: two when 128-row panels still give
 // every CU at least two tiles to walk, else one.
@@ -131,7 +146,7 @@ void fill_spmm_slab_info(int m, int k, int n, int nnz, int variant, spdl_launch_
   const int rpg = (variant == kSpmmSlabDma && !half) ? slab_rows_per_group(m, n) : 1;
   const int rows = (half ? kSlabRows / 2 : kSlabRows) * rpg;
   const int panels = (m + rows - 1) / rows;
-  int tpw = slab_tiles_per_wg(panels, tiles);
+  int tpw = slab_tiles_per_wg(panels, tiles, half ? 2 * kComputeUnits : kComputeUnits);
   // wide outputs, two rows per group: the tile-inner kernel, at most kSlabTilesMax tiles per workgroup
   if (rpg == 2 && tpw >= 2 && slab_tiles_fits(m, k, nnz)) tpw = std::min(tpw, kSlabTilesMax);
   const int groups = (tiles + tpw - 1) / tpw;
@@ -444,8 +459,7 @@ SddmmSlabShape sddmm_slab_shape(int m, int k, int n) {
   sh.S = 256 / sh.U;
   sh.panels = (m + kSdRows - 1) / kSdRows;
   const int total = std::max(1, (k + sh.S - 1) / sh.S);
-  const int want = std::max(1, std::min(total, (kComputeUnits + sh.panels - 1) / sh.panels));
-  sh.spp = (total + want - 1) / want;
+  sh.spp = split_for_machine(sh.panels, total);
   sh.ksplit = (total + sh.spp - 1) / sh.spp;
   sh.lds_bytes = 2 * (sh.S + 1) * 256 * sh.U;
   return sh;
@@ -470,8 +484,7 @@ SddmmLaneShape sddmm_lane_shape(int m, int k, int nnz, bool one_row_per_group = 
   if (one_row_per_group) sh.rpg = 1;
   sh.panels = (m + kSdRows * sh.rpg - 1) / (kSdRows * sh.rpg);
   const int total = std::max(1, (k + kLaneS - 1) / kLaneS);
-  const int want = std::max(1, std::min(total, (kComputeUnits + sh.panels - 1) / sh.panels));
-  sh.spp = (total + want - 1) / want;
+  sh.spp = split_for_machine(sh.panels, total);
   sh.ksplit = (total + sh.spp - 1) / sh.spp;
   return sh;
 }

@@ -317,3 +317,29 @@ def test_workload_statistics():
         for i in range(0, A_.m, 97):
             c = A_.column_indices[A_.row_offsets[i]:A_.row_offsets[i + 1]]
             assert np.all(np.diff(c) > 0) and (len(c) == 0 or (c[0] >= 0 and c[-1] < A_.k))
+
+
+def test_work_split_per_panel_avoids_a_second_round_of_workgroups():
+    """A slab kernel's workgroup fills a compute unit, so more than 256 workgroups run in rounds:
+    the split of a panel's work (column ranges of A in SDDMM, tiles of C in SpMM) is the one with
+    the shortest chain, not the one with the most workgroups."""
+    import paper_2006_10901_amd as spdl
+    names = {spdl.spdl_variant_name(1, v): v for v in range(16) if spdl.spdl_variant_name(1, v)}
+    try:
+        for variant in ("slabdma", "lane"):
+            spdl.spdl_force_variant(1, names[variant])
+            # 64 panels: four column ranges each, one workgroup per compute unit (the LSTM and FFN shapes)
+            info = spdl.spdl_select_sddmm(4096, 4096, 256, 4096 * 400, 4, 0, 0)
+            assert (info["grid_x"], info["grid_y"]) == (256, 4)
+            # 48 panels: five ranges (240 workgroups), not six (288: a second round for 32 of them)
+            info = spdl.spdl_select_sddmm(3072, 3072, 256, 3072 * 300, 4, 0, 0)
+            assert (info["grid_x"], info["grid_y"]) == (240, 5)
+            # 96 panels: two ranges, not three
+            info = spdl.spdl_select_sddmm(6144, 2048, 256, 6144 * 200, 4, 0, 0)
+            assert (info["grid_x"], info["grid_y"]) == (192, 2)
+    finally:
+        spdl.spdl_force_variant(1, -1)
+    info = spdl.spdl_select_spmm(8192, 10240, 128, 8390433, 4, 0, 0)        # the LSTM problem: unchanged
+    assert spdl.spdl_variant_name(0, info["variant"]) == "slabdma" and info["grid_x"] == 256
+    info = spdl.spdl_select_spmm(3072, 3072, 1024, 3072 * 300, 4, 0, 0)     # 48 panels, 16 tiles: 4 x 4 tiles, not 6 x 3
+    assert spdl.spdl_variant_name(0, info["variant"]) == "slabdma" and info["grid_x"] == 192
