@@ -98,16 +98,18 @@ bool slab_usable(int n, int nnz, const void* B, const void* C) {
 // A slab kernel's workgroup fills a compute unit (LDS), so a grid of more than `slots` workgroups
 // runs in rounds.  `total` units of work per panel (tiles of C, slabs of A's columns), walked back
 // to back by one workgroup, are dealt to the number of workgroups per panel that gives the shortest
-// chain: rounds x (units per workgroup + two units' worth of set-up).  (3072 rows, 48 panels: six
-// workgroups per panel would be 288, a second round for 32 of them; five make 240 in one round.)
-// Returns the units per workgroup.
+// chain: rounds x (units per workgroup + two units' worth of set-up).  All workgroups of a panel
+// run on the same XCD (slab_wg_map), so the rounds are those of the XCD with the most panels.
+// (3072 rows, 48 panels, six per XCD: six workgroups per panel would be 36 on each XCD's 32 compute
+// units, a second round for four of them; five make 30 in one round.)  Returns the units per
+// workgroup.
 int split_for_machine(int panels, int total, int slots = kComputeUnits) {
   int best_units = total;
   double best = 1e300;
   for (int parts = 1; parts <= std::min(total, slots); ++parts) {
     const int units = (total + parts - 1) / parts;
-    const int64_t wgs = (int64_t)panels * ((total + units - 1) / units);
-    const double cost = (double)((wgs + slots - 1) / slots) * (units + 2.0);
+    const int64_t wgs = (int64_t)((panels + 7) / 8) * ((total + units - 1) / units);    // on the fullest XCD
+    const double cost = (double)((wgs + slots / 8 - 1) / (slots / 8)) * (units + 2.0);
     if (cost < best - 1e-9) {
       best = cost;
       best_units = units;
@@ -249,7 +251,16 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
     // (Wide outputs that leave half the compute units without a full-size workgroup run the slab kernel
     // with workgroups of 8 waves and twice as many stages: 4096 x 4096 at 6 % density, n = 128: 31 us
     // against 24 for the window kernel's gathers; at 12 % 39 against 42.)
-    const double min_reuse = n <= 32 ? 12.0 : (n <= 64 || out_tiles < kComputeUnits) ? 5.0 : 2.0;
+    // (Two to four tiles and a B of fewer than 8192 rows, which the gathers then find in L2: the slab
+    // kernel pays from 64 * density = 3 on; 16995 x 3895 at 3.2 %, n = 128: 89 us against 62 for
+    // row-splitting, 5006 x 2875 at 4.1 %, n = 256: 38 against 26, while the LSTM matrix at 95 %
+    // sparsity, 10240 columns, runs 1.4 times faster in it.  Eight tiles or more, scanned once per
+    // slab for several tiles: from 1.8 on; 15161 x 5174 at 2.9 %, n = 1024: 321 us against 413.)
+    const double min_reuse = n <= 32                                          ? 12.0
+                             : (n <= 64 || out_tiles < kComputeUnits)         ? 5.0
+                             : (n <= 4 * kSlabTile && k < 8192)               ? 3.0
+                             : n >= 8 * kSlabTile                             ? 1.8
+                                                                              : 2.0;
     // (Dense matrices gain so much from the slab kernel that it pays with most compute units idle:
     // 6144 x 2048 at 35 %, n = 64, 96 workgroups: 36 us against 54 for row-splitting; 4096 x 4096 at
     // 50 %, 64 workgroups: 87 against 98; at 20 % and 35 % respectively the two are level.)
@@ -280,6 +291,16 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
         n > 32 && n <= 2 * kWinTile &&
         ((m >= 4096 && (double)nnz >= 100.0 * (double)m) ||
          (m >= 2048 && (double)nnz >= (n > kWinTile ? 192.0 : 400.0) * (double)m)))
+      variant = kSpmmWindow;
+    // Wider outputs (one workgroup per 64-column tile): the workgroups at work on one tile share
+    // k x 256 bytes of B.  While that stays in L2 the row-splitting kernel is as fast or faster; with
+    // 7000 columns or more and rows of 120 entries or more the window kernel's sixteen gathers in
+    // flight per wave hide the longer latency better (15796 x 11092 at 1.2 %, n = 256: 116 us against
+    // 175; 19428 x 9075 at 2.1 %, n = 1024: 636 against 1108; 13651 x 3925 at 3.1 %, n = 256: 98
+    // against 69, not taken).
+    if (variant == kSpmmRowsplit && sizeof(T) == 4 && slab_usable<T>(n, nnz, B, C) &&
+        (int64_t)k * n < ((int64_t)1 << 29) && n > 2 * kWinTile && m >= 4096 && k >= 7000 &&
+        (double)nnz >= 120.0 * (double)m)
       variant = kSpmmWindow;
     // the caller says that the entries form a band (a problem the window kernel cannot take keeps
     // the choice made above)
@@ -591,10 +612,12 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
       const double flops = 2.0 * (double)nnz * (double)n;                   // per launch, all passes
       const int passes = (n + 127) / 128;
       const double t_lane = passes * 9.5 + flops / (rate(lane_rate) * 1e6);   // microseconds
-      const double t_slab = 8.0 + flops / (rate(slab_rate) * 1e6);
+      // (every panel of 64 rows streams all of R through its compute unit: 8 TB/s over the chip at best)
+      const double panels64 = (double)((m + kSdRows - 1) / kSdRows);
+      const double t_slab = 8.0 + std::max(flops / (rate(slab_rate) * 1e6), panels64 * (double)k * (double)n * 4.0 / 8.0e6);
       // (a strip of the gather kernel steps through its dot product 64 columns at a time, about 1.1 us
       // of memory latency per step: the floor for small problems)
-      const double t_group = 5.0 + 1.1 * (double)(n / 64) + flops / 6.0e6;
+      const double t_group = 5.0 + 1.1 * (double)(n / 64) + flops / 7.0e6;
       variant = (t_lane <= t_slab && t_lane <= t_group) ? kSddmmLane : t_slab <= t_group ? kSddmmSlabDma : kSddmmGroup;
     }
   }

@@ -201,8 +201,13 @@ def test_spmm_selection_of_the_window_kernel(spdl):
     assert chosen(8192, 10240, 128, 4195643) == "slabdma"         # ... at 95 %
     assert chosen(2048, 4096, 128, 2048 * 400) == "window"
     assert chosen(1024, 4096, 128, 1024 * 400) == "rowsplit"      # too few rows
-    assert chosen(4096, 4096, 256, 4096 * 246) == "slabdma"       # wider than two tiles: never the window kernel
-    assert chosen(4096, 65536, 256, 4096 * 246) == "rowsplit"
+    assert chosen(4096, 4096, 256, 4096 * 246) == "slabdma"
+    # wider than two tiles: the window kernel only where a tile's share of B (k x 256 bytes) is too large for L2
+    assert chosen(4096, 65536, 256, 4096 * 246) == "window"
+    assert chosen(16384, 6000, 256, 16384 * 100) == "rowsplit"
+    assert chosen(16384, 12000, 256, 16384 * 100) == "rowsplit"   # rows too short
+    assert chosen(16384, 12000, 256, 16384 * 130) == "window"
+    assert chosen(16384, 12000, 1024, 16384 * 130) == "window"
     assert chosen(4096, 4096, 64, int(4096 * 4096 * 0.3)) == "window"       # denser, still no slab shape: gathers
     assert chosen(2048, 2048, 64, 2048 * 300) == "rowsplit"       # few rows and not long enough
     assert chosen(2048, 2048, 64, 2048 * 400) == "window"
