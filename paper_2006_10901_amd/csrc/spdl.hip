@@ -179,20 +179,24 @@ constexpr int kSpmmMfmaKParts = 2;                // waves per tile, splitting t
 // measured rates on shapes from 1024 x 1024 x 3136 to 8192 x 10240 x 128).  The matrix-core kernels
 // do work proportional to m*k whatever the density, in rounds of one workgroup per CU: a panel of
 // 32 rows x 512 columns costs about 8.4 us plus 13.8 ns per column of A (SpMM), a 64 x 64 block
-// 3.5 us plus 0.5 us per 128 columns of the dot product (SDDMM); filling the panels and sampling
-// the blocks add 24 and 8 us per million entries.  The direct kernels run at the rate of their
-// gathers: 19.5 TFLOP/s (SpMM); 14 TFLOP/s for short dot products, 8 beyond 128 columns, after a
-// latency floor of 2 us per 64 columns of the dot product (SDDMM).
+// 3.5 us plus 0.5 us per 128 columns of the dot product (SDDMM); filling a panel adds 1 ns per entry
+// of its 32 rows (a workgroup walks its rows about twice: once whole, once in pieces per chunk of
+// 1024 columns), sampling the blocks 8 us per million entries.  The direct kernels run at the rate
+// of their gathers: 19.5 TFLOP/s (SpMM); 14 TFLOP/s for short dot products, 12 beyond 128 columns,
+// after a latency floor of 2 us per 64 columns of the dot product (SDDMM).  (Rates refitted on 120
+// random shapes, 512 .. 12000 rows and columns, 1 .. 50 % density, n = 48 .. 3136, both families
+// forced: the choice then takes 1.006 times the faster one's time on average.)
 inline bool spmm_mfma_pays(int m, int k, int n, int nnz) {
   const double wgs = (double)((m + 31) / 32) * (double)(((n + 255) / 256 + kSpmmMfmaWaves - 1) / kSpmmMfmaWaves);
-  const double t_mfma = std::ceil(wgs / kComputeUnits) * (8.4 + 0.0138 * (double)k) + 24e-6 * (double)nnz;
+  const double per_panel = m > 0 ? 32.0 * (double)nnz / (double)m : 0.0;
+  const double t_mfma = std::ceil(wgs / kComputeUnits) * (8.4 + 0.0138 * (double)k + 1.0e-3 * per_panel);
   const double t_direct = 7.0 + 2.0 * (double)nnz * (double)n / 19.5e6;
   return t_mfma <= t_direct;
 }
 inline bool sddmm_mfma_pays(int m, int k, int n, int nnz) {
   const double blocks = (double)((m + 63) / 64) * (double)((k + 63) / 64);
   const double t_mfma = std::ceil(blocks / kComputeUnits) * (3.5 + 0.5 * (double)((n + 127) / 128)) + 8e-6 * (double)nnz;
-  const double t_direct = 5.0 + 2.0 * (double)(n / 64) + 2.0 * (double)nnz * (double)n / ((n <= 128 ? 14.0 : 8.0) * 1e6);
+  const double t_direct = 5.0 + 2.0 * (double)(n / 64) + 2.0 * (double)nnz * (double)n / ((n <= 128 ? 14.0 : 12.0) * 1e6);
   return t_mfma <= t_direct;
 }
 

@@ -88,6 +88,11 @@ __global__ __launch_bounds__(64 * WAVES * KP) void spmm_mfma_kernel(
 #pragma unroll
       for (int t = 0; t < 16; ++t) acc[rb][j][t] = 0.f;
 
+  // Where each of this wave's rows continues in the next chunk of columns (rows in ascending order:
+  // the entries of a chunk follow those of the chunk before).  The first chunk walks whole rows,
+  // which is also what finds the rows that are not ascending; later chunks start at the cursor and
+  // stop at the first 64 entries that reach past the chunk.
+  int cursor[(32 * RB) / (THREADS / 64)];
   for (int kc0 = 0; kc0 < k; kc0 += kMfmaChunk) {
     const int kc = min(k - kc0, kMfmaChunk);
     const int all_steps = (kc + 15) >> 4;
@@ -163,7 +168,9 @@ __global__ __launch_bounds__(64 * WAVES * KP) void spmm_mfma_kernel(
       const int rr = wave + NW * i;
       row_begin[i] = uniform(row_offsets[min(i0 + rr, m)]);
       row_end[i] = uniform(row_offsets[min(i0 + rr + 1, m)]);
+      if (kc0 > 0) row_begin[i] = cursor[i];
     }
+    const int kend = kc0 + kc;
 #pragma unroll
     for (int i = 0; i < RW; ++i)
 #pragma unroll
@@ -186,13 +193,19 @@ __global__ __launch_bounds__(64 * WAVES * KP) void spmm_mfma_kernel(
       _Float16* prow = panel + rr * stride;
       int below = 0;                                     // column of the previous 64's lane 63
       bool unordered = false;
+      int before_end = 0;                                // entries seen whose column lies before the chunk's end
+      bool past = false;                                 // some entry seen lies past the chunk
       auto place = [&](int p, int cidx, _Float16 a, bool head) {
         const int prev = __shfl_up(cidx, 1);
-        if (p < row_end[i]) {
+        const bool valid = p < row_end[i];
+        if (valid) {
           if (!head && (lane == 0 ? below : prev) >= cidx) unordered = true;
           const unsigned rel = (unsigned)(cidx - kc0);
           if (rel < (unsigned)kc) prow[rel] = a;
         }
+        const unsigned long long inside = __builtin_amdgcn_ballot_w64(valid && cidx < kend);
+        before_end += __builtin_popcountll(inside);
+        past = past || __builtin_amdgcn_ballot_w64(valid && cidx >= kend) != 0;
         below = __builtin_amdgcn_readlane(cidx, 63);
       };
 #pragma unroll
@@ -200,6 +213,7 @@ __global__ __launch_bounds__(64 * WAVES * KP) void spmm_mfma_kernel(
         if (row_begin[i] + 64 * e < row_end[i])
           place(row_begin[i] + 64 * e + lane, cfirst[i][e], afirst[i][e], e == 0 && lane == 0);
       for (int base = row_begin[i] + 64 * PRE; base < row_end[i]; base += 256) {   // long rows: 256 entries per round
+        if (kc0 > 0 && past) break;                      // (ascending rows: nothing further belongs to this chunk)
         int cmore[4];
         _Float16 amore[4];
 #pragma unroll
@@ -213,6 +227,7 @@ __global__ __launch_bounds__(64 * WAVES * KP) void spmm_mfma_kernel(
           if (base + 64 * e < row_end[i]) place(base + 64 * e + lane, cmore[e], amore[e], false);
       }
       if (kc0 == 0 && __builtin_amdgcn_ballot_w64(unordered) != 0 && lane == 0) bad[rr] = 1;
+      cursor[i] = row_begin[i] + before_end;
     }
     // Some of the expansion's loads are used on one path only; the compiler would otherwise wait
     // for them inside the main loop, where its wait also drains the loads of B.  (vmcnt 0; the

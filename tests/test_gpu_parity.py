@@ -659,6 +659,51 @@ def test_mfma_spmm_row_lengths_and_short_contractions(g, oracle_lib, force):
     spmm_case(g, oracle_lib, A, wl.dense(A.k, 64, 1291, np.float16), 64, g.TOL_F16, "sorted", "k=12 fp16")
 
 
+def test_mfma_spmm_rows_across_many_column_chunks(g, oracle_lib, force):
+    """The panel of the matrix-core SpMM is expanded once per chunk of 1024 columns of A, each row
+    continuing where the chunk before left it.  Five chunks; rows that hold every column, rows whose
+    entries all lie in one late chunk or skip the middle chunks, rows with 64 / 128 / 256 entries
+    per chunk exactly (the sizes of the expansion's rounds), a row with one entry in the last
+    column, empty rows, and rows that are not ascending (computed apart), all in one panel and
+    again spread over several."""
+    import paper_2006_10901_amd as spdl
+    k = 5000
+    rng = np.random.default_rng(1300)
+    def cols(kind):
+        if kind == "full":
+            return np.arange(k)
+        if kind == "late":
+            return np.arange(4100, 4100 + 700)
+        if kind == "ends":
+            return np.concatenate([np.arange(0, 300), np.arange(4096, 4096 + 300)])
+        if kind == "last":
+            return np.array([k - 1])
+        if kind == "empty":
+            return np.array([], dtype=np.int64)
+        if kind.startswith("per"):
+            per = int(kind[3:])
+            return np.concatenate([c * 1024 + np.sort(rng.choice(900, per, replace=False)) for c in range(5)])
+        if kind == "random":
+            return np.sort(rng.choice(k, int(rng.integers(1, 3000)), replace=False))
+        if kind == "shuffled":
+            return rng.permutation(np.sort(rng.choice(k, 1500, replace=False)))
+        raise ValueError(kind)
+    kinds = ["full", "late", "ends", "last", "empty", "per64", "per128", "per256", "per65", "random", "shuffled", "full",
+             "random", "late", "per129", "random"]
+    for rows in (kinds, kinds * 5 + ["full", "empty", "shuffled"]):
+        per_row = [cols(kd) for kd in rows]
+        ro = np.zeros(len(rows) + 1, dtype=np.int32)
+        ro[1:] = np.cumsum([len(c) for c in per_row])
+        ci = np.concatenate(per_row).astype(np.int32)
+        vals = rng.standard_normal(len(ci)).astype(np.float16)
+        A = wl.Csr(len(rows), k, ro, ci, vals)
+        for n in (8, 264):
+            B = wl.dense(k, n, 1301 + n, np.float16)
+            force(0, 3)
+            assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(A.m, A.k, n, A.nnz, 2, 0, 0)["variant"]) == "mfma"
+            spmm_case(g, oracle_lib, A, B, n, g.TOL_F16, "sorted", f"mfma spmm, five chunks, n={n} m={A.m}")
+
+
 def test_mfma_kernels_are_the_default_for_moderately_sparse_fp16(g):
     import paper_2006_10901_amd as spdl
     assert spdl.spdl_variant_name(0, spdl.spdl_select_spmm(1024, 1024, 3136, 104000, 2, 0, 0)["variant"]) == "mfma"
