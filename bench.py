@@ -248,6 +248,22 @@ def extra_cases(groups, wl, spdl, torch):
             f32 = lambda a: a.astype(np.float32)
             extra.append(Case(nm, "spmm", A32, 3136, (f32(w["B"]),), spdl, torch))
             extra.append(Case(nm, "sddmm", A32, 3136, (f32(w["L"]), f32(w["R"])), spdl, torch))
+            if skew:
+                # ... and through the entry points for rows of strongly unequal length
+                ro, ci, val = dev(A32.row_offsets), dev(A32.column_indices), dev(A32.values)
+                B, L, R = dev(f32(w["B"])), dev(f32(w["L"])), dev(f32(w["R"]))
+                C = torch.empty((A32.m, 3136), device="cuda")
+                out = torch.empty(A32.nnz, device="cuda")
+                extra.append(WidenedCase(nm, "spmm_skewed", "by hint", A32.nnz,
+                                         lambda A=A32, ro=ro, ci=ci, val=val, B=B, C=C:
+                                         spdl.spdl_spmm_skewed(A.m, A.k, 3136, A.nnz, ro, ci, val, B, C),
+                                         spmm_bytes(A32.m, A32.k, 3136, A32.nnz), 2.0 * A32.nnz * 3136,
+                                         dims=(A32.m, A32.k, 3136)))
+                extra.append(WidenedCase(nm, "sddmm_skewed", "by hint", A32.nnz,
+                                         lambda A=A32, ro=ro, ci=ci, L=L, R=R, out=out:
+                                         spdl.spdl_sddmm_skewed(A.m, A.k, 3136, A.nnz, ro, ci, L, R, out),
+                                         sddmm_bytes(A32.m, A32.k, 3136, A32.nnz), 2.0 * A32.nnz * 3136,
+                                         dims=(A32.m, A32.k, 3136)))
     if "imbalance" in groups:
         # Load imbalance (the paper's load-imbalance figure): 8192 x 2048 at 75 % sparsity, n = 128,
         # equal row lengths against gamma-distributed ones (coefficient of variation about 1),

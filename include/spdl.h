@@ -83,11 +83,29 @@ int spdl_sddmm(int m, int k, int n, int nnz, const int* row_offsets, const int* 
  * found on the device; without a band every entry is gathered and the result is still right.
  * Used as given for fp32 with n % 4 == 0, 16-byte aligned dense operands and k*n < 2^29 (SDDMM:
  * n <= 128); any other problem runs exactly as through spdl_spmm / spdl_sddmm.  spdl_spmm and
- * spdl_sddmm themselves pick these kernels for 33..64 columns, 4096 rows or more, 192 entries
- * per row or more and at most 1/8 density. */
+ * spdl_sddmm pick these kernels themselves for shapes like that of an attention head (thousands of
+ * rows of a hundred entries or more, 33..128 columns), where they are also the faster way to
+ * gather. */
 int spdl_spmm_banded(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                      const float* values, const float* B, float* C, void* stream);
 int spdl_sddmm_banded(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                      const float* L, const float* R, float* out_values, void* stream);
+
+/* SpMM and SDDMM for a sparse matrix whose rows are of strongly unequal length (a few rows of
+ * thousands of entries among rows of tens or hundreds: the heavy-tailed row lengths that paper
+ * Sec. "Row Swizzle Load Balancing" is about, beyond what reordering rows evens out).  Same
+ * operations, arguments and results as spdl_spmm (without a row order) and spdl_sddmm; the only
+ * difference is the choice of kernel, which the library cannot make by itself because it never
+ * reads the row lengths on the host: kernels whose work per wave does not depend on the length of
+ * a row (SpMM: a wave per row, what a row holds beyond its share dealt to all waves of the
+ * workgroup; SDDMM: the entries split evenly over the waves, or for dot products of more than 256
+ * columns the kernel estimated faster without the one that keeps partial sums per row).  fp32,
+ * n % 4 == 0, 16-byte aligned dense operands and k*n < 2^29; any other problem runs exactly as
+ * through spdl_spmm / spdl_sddmm.  On matrices with rows of similar length these entry points are
+ * up to twice as slow as spdl_spmm / spdl_sddmm. */
+int spdl_spmm_skewed(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                     const float* values, const float* B, float* C, void* stream);
+int spdl_sddmm_skewed(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                       const float* L, const float* R, float* out_values, void* stream);
 
 /* SDDMM with the row order of SpMM (paper Sec. "Row Swizzle Load Balancing"; the paper applies the

@@ -22,7 +22,7 @@ EXPORTS = (
     "spdl_spmm_bias_relu", "spdl_spmm_bias_relu_f16", "spdl_csr_softmax", "spdl_build_transpose_host",
     "spdl_permute_values", "spdl_sddmm_scaled", "spdl_sddmm_scaled_f16",
     "spdl_sddmm_nt", "spdl_sddmm_nt_f16", "spdl_spmm_f16_i16", "spdl_sddmm_ordered",
-    "spdl_spmm_banded", "spdl_sddmm_banded",
+    "spdl_spmm_banded", "spdl_sddmm_banded", "spdl_spmm_skewed", "spdl_sddmm_skewed",
 )
 
 
@@ -129,6 +129,25 @@ def spdl_sddmm_banded(m, k, n, nnz, row_offsets, column_indices, L, R, out_value
         _dev(column_indices, torch.int32, "column_indices"), _dev(L, torch.float32, "L"),
         _dev(R, torch.float32, "R"), _dev(out_values, torch.float32, "out_values"), _stream(stream)),
         "spdl_sddmm_banded")
+    return out_values
+
+
+def spdl_spmm_skewed(m, k, n, nnz, row_offsets, column_indices, values, B, C, stream=None):
+    import torch
+    _check(lib().spdl_spmm_skewed(
+        int(m), int(k), int(n), int(nnz), _dev(row_offsets, torch.int32, "row_offsets"),
+        _dev(column_indices, torch.int32, "column_indices"), _dev(values, torch.float32, "values"),
+        _dev(B, torch.float32, "B"), _dev(C, torch.float32, "C"), _stream(stream)), "spdl_spmm_skewed")
+    return C
+
+
+def spdl_sddmm_skewed(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stream=None):
+    import torch
+    _check(lib().spdl_sddmm_skewed(
+        int(m), int(k), int(n), int(nnz), _dev(row_offsets, torch.int32, "row_offsets"),
+        _dev(column_indices, torch.int32, "column_indices"), _dev(L, torch.float32, "L"),
+        _dev(R, torch.float32, "R"), _dev(out_values, torch.float32, "out_values"), _stream(stream)),
+        "spdl_sddmm_skewed")
     return out_values
 
 

@@ -32,6 +32,8 @@ namespace {
 using namespace spdl;
 
 enum SpmmVariant { kSpmmRowsplit = 0, kSpmmSlab = 1, kSpmmSlabDma = 2, kSpmmMfma = 3, kSpmmWindow = 4, kSpmmVariants };
+// What the caller says about the sparse matrix (the library never reads the topology on the host).
+enum Hint { kHintNone = 0, kHintBanded = 1, kHintSkewed = 2 };
 enum SddmmVariant { kSddmmRowstrip = 0, kSddmmGroup = 1, kSddmmSlab = 2, kSddmmSlabDma = 3, kSddmmMfma = 4, kSddmmLane = 5, kSddmmWindow = 6, kSddmmVariants };
 
 std::atomic<int> g_forced[2] = {{-1}, {-1}};
@@ -220,7 +222,7 @@ bool spmm_mfma_runnable() {
 
 template <typename T>
 void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, spdl_launch_info* info,
-                    bool banded = false) {
+                    int hint = 0) {
   int variant = g_forced[0].load();
   const bool mfma_ok = sizeof(T) == 2 && n % 8 == 0 && n < (1 << 24) && k >= 16 && aligned(B, 16) && aligned(C, 16);
   // nnz == 0: column_indices, values and B may be null, and the slab and matrix-core kernels
@@ -306,10 +308,15 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
         (int64_t)k * n < ((int64_t)1 << 29) && n > 2 * kWinTile && m >= 4096 && k >= 7000 &&
         (double)nnz >= 120.0 * (double)m)
       variant = kSpmmWindow;
-    // the caller says that the entries form a band (a problem the window kernel cannot take keeps
-    // the choice made above)
-    if (banded && sizeof(T) == 4 && nnz > 0 && slab_usable<T>(n, nnz, B, C) && (int64_t)k * n < ((int64_t)1 << 29))
+    // the caller says that the entries form a band, or that the row lengths are strongly unequal: the
+    // window kernel gathers what is not in a band and shares long rows among the waves of a workgroup
+    // (a problem the window kernel cannot take keeps the choice made above)
+    if (hint != kHintNone && sizeof(T) == 4 && nnz > 0 && slab_usable<T>(n, nnz, B, C) && (int64_t)k * n < ((int64_t)1 << 29))
       variant = kSpmmWindow;
+    // (unequal rows, more than two tiles and a B of fewer than 4000 rows, whose share per tile the
+    // gathers find in L2: row-splitting, 1.2 .. 2.4 times faster there than the window kernel, while the
+    // slab kernels wait for their longest row)
+    if (hint == kHintSkewed && n > 2 * kWinTile && k < 4000) variant = kSpmmRowsplit;
   }
   if (variant == kSpmmWindow && sizeof(T) == 4 && nnz > 0 && slab_usable<T>(n, nnz, B, C) &&
       (int64_t)k * n < ((int64_t)1 << 29)) {
@@ -374,13 +381,13 @@ int launch_spmm_rowsplit(const spdl_launch_info& li, int m, int n, const int* ro
 template <typename T, typename I = int>
 int spmm_impl(int m, int k, int n, int nnz, const int* ro, const I* ci, const T* val,
               const int* order, const T* B, T* C, void* stream, const T* bias = nullptr, int relu = 0,
-              bool banded = false) {
+              int hint = 0) {
   if (!sizes_ok(m, k, n, nnz)) return SPDL_ERR_INVALID;
   if (m == 0 || n == 0) return SPDL_OK;
   if (!ro || !C || (nnz > 0 && (!ci || !val || !B))) return SPDL_ERR_INVALID;
   hipStream_t st = static_cast<hipStream_t>(stream);
   spdl_launch_info li;
-  fill_spmm_info<T>(m, k, n, nnz, B, C, &li, banded);
+  fill_spmm_info<T>(m, k, n, nnz, B, C, &li, hint);
   (void)hipGetLastError();
   int rc = SPDL_OK;
   constexpr bool kInt32 = sizeof(I) == 4;        // the slab kernels read 32-bit indices only
@@ -544,7 +551,7 @@ bool sddmm_lane_usable(int n, int nnz, const void* L, const void* R) {
 
 template <typename T>
 void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R, spdl_launch_info* info,
-                     bool banded = false) {
+                     int hint = 0) {
   const bool fast_ok = sddmm_group_usable<T>(n, L, R);
   int variant = g_forced[1].load();
   const bool free_choice = variant < 0;
@@ -564,6 +571,7 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
     info->grid_y = (k + 63) / 64;               // 64-column blocks per panel (the grid is 1-D)
     return;
   }
+  bool skewed_lane = false;      // (for the hint of unequal rows) lane kernel estimated faster than the nonzero-split one
   if (variant < 0) {
     const double density = (m > 0 && k > 0) ? (double)nnz / ((double)m * (double)k) : 0.0;
     const double reuse = 64.0 * density;
@@ -623,6 +631,8 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
       // of memory latency per step: the floor for small problems)
       const double t_group = 5.0 + 1.1 * (double)(n / 64) + flops / 7.0e6;
       variant = (t_lane <= t_slab && t_lane <= t_group) ? kSddmmLane : t_slab <= t_group ? kSddmmSlabDma : kSddmmGroup;
+      // (the lane kernel's rate is that of rows of equal length; an R of a few megabytes is gathered from L2)
+      skewed_lane = t_lane <= 0.45 * t_group && (double)k * (double)n * 4.0 >= 7.0e6;
     }
   }
   if ((variant == kSddmmSlab || variant == kSddmmSlabDma) &&
@@ -633,7 +643,13 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
                          (int64_t)k * n < ((int64_t)1 << 29);
   // the caller says that the entries form a band (a problem the window kernel cannot take keeps the
   // choice made above)
-  if (free_choice && banded && window_ok) variant = kSddmmWindow;
+  if (free_choice && hint == kHintBanded && window_ok) variant = kSddmmWindow;
+  // the caller says that the row lengths are strongly unequal: the nonzero-split kernel, which does not
+  // care, or for dot products of more than 128 columns the lane kernel in passes where the estimate
+  // above gives it less than 0.45 of that kernel's time (dense matrices; the slab kernel, whose
+  // deferred partial sums overflow on the long rows, is left out)
+  if (free_choice && hint == kHintSkewed && fast_ok && (variant == kSddmmLane || variant == kSddmmSlabDma || variant == kSddmmWindow))
+    variant = skewed_lane ? kSddmmLane : kSddmmGroup;
   if (variant == kSddmmWindow && !window_ok) variant = kSddmmGroup;
   if (variant == kSddmmGroup && !fast_ok) variant = kSddmmRowstrip;
   const int avg = m > 0 ? nnz / m : 0;
@@ -723,13 +739,13 @@ int launch_sddmm_slab(const SddmmSlabShape& sh, int grid, int m, int k, int n, i
 
 template <typename T>
 int sddmm_impl(int m, int k, int n, int nnz, const int* ro, const int* ci, const T* L, const T* R,
-               T* out, void* stream, const T* scale = nullptr, const int* order = nullptr, bool banded = false) {
+               T* out, void* stream, const T* scale = nullptr, const int* order = nullptr, int hint = 0) {
   if (!sizes_ok(m, k, n, nnz)) return SPDL_ERR_INVALID;
   if (m == 0 || nnz == 0) return SPDL_OK;
   if (!ro || !ci || !out || (n > 0 && (!L || !R))) return SPDL_ERR_INVALID;
   hipStream_t st = static_cast<hipStream_t>(stream);
   spdl_launch_info li;
-  fill_sddmm_info<T>(m, k, n, nnz, L, R, &li, banded);
+  fill_sddmm_info<T>(m, k, n, nnz, L, R, &li, hint);
   dim3 grid(li.grid_x), block(256);
   const int split = li.rows_per_block;
   (void)hipGetLastError();
@@ -955,12 +971,22 @@ int spdl_sddmm(int m, int k, int n, int nnz, const int* row_offsets, const int* 
 
 int spdl_spmm_banded(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                      const float* values, const float* B, float* C, void* stream) {
-  return spmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, values, nullptr, B, C, stream, nullptr, 0, true);
+  return spmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, values, nullptr, B, C, stream, nullptr, 0, kHintBanded);
 }
 
 int spdl_sddmm_banded(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
                       const float* L, const float* R, float* out_values, void* stream) {
-  return sddmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stream, nullptr, nullptr, true);
+  return sddmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stream, nullptr, nullptr, kHintBanded);
+}
+
+int spdl_spmm_skewed(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                     const float* values, const float* B, float* C, void* stream) {
+  return spmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, values, nullptr, B, C, stream, nullptr, 0, kHintSkewed);
+}
+
+int spdl_sddmm_skewed(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,
+                      const float* L, const float* R, float* out_values, void* stream) {
+  return sddmm_impl<float>(m, k, n, nnz, row_offsets, column_indices, L, R, out_values, stream, nullptr, nullptr, kHintSkewed);
 }
 
 int spdl_sddmm_ordered(int m, int k, int n, int nnz, const int* row_offsets, const int* column_indices,

@@ -604,6 +604,36 @@ def test_spmm_wide_outputs_tile_inner_slab_kernel(g, oracle_lib, force):
     g.assert_close(out.cpu().numpy(), C, S, g.TOL_F32, "tile-inner slab, bias + ReLU")
 
 
+def test_entry_points_for_rows_of_unequal_length(g, oracle_lib):
+    """spdl_spmm_skewed / spdl_sddmm_skewed: the same results as spdl_spmm / spdl_sddmm through the
+    kernels that do not care how long a row is.  Log-normal row lengths (a few rows of thousands of
+    entries), short and long dot products, a shape the preferred kernels cannot take (n % 4 != 0:
+    runs as through the plain entry points), an empty matrix."""
+    import torch
+    import paper_2006_10901_amd as spdl
+    cases = [(wl.lognormal_rows_csr(3000, 4000, 0.05, 5100, sigma_ln=1.5), 64),
+             (wl.lognormal_rows_csr(2500, 3000, 0.08, 5101, sigma_ln=1.2), 128),
+             (wl.lognormal_rows_csr(1500, 2100, 0.06, 5102, sigma_ln=1.3), 200),
+             (wl.lognormal_rows_csr(1300, 1700, 0.10, 5103, sigma_ln=1.0), 520),
+             (wl.lognormal_rows_csr(700, 900, 0.10, 5104, sigma_ln=1.0), 30),
+             (wl.uniform_mask_csr(40, 50, 0.0, 5105), 64)]
+    for A, n in cases:
+        what = f"m={A.m} k={A.k} n={n} nnz={A.nnz}"
+        d = g.DevCsr(A)
+        B = wl.dense(A.k, n, 5110 + n)
+        C, S = oracle_lib.spmm(A.m, A.k, n, A.row_offsets, A.column_indices, A.values, B)
+        out = torch.full((A.m, n), float("nan"), dtype=torch.float32, device="cuda")
+        spdl.spdl_spmm_skewed(A.m, A.k, n, A.nnz, d.ro, d.ci, d.val, g.dev(B), out)
+        torch.cuda.synchronize()
+        g.assert_close(out.cpu().numpy(), C, S, g.TOL_F32, "spmm_skewed " + what)
+        L, R = wl.dense(A.m, n, 5111 + n), wl.dense(A.k, n, 5112 + n)
+        ref, S = oracle_lib.sddmm(A.m, A.k, n, A.row_offsets, A.column_indices, L, R)
+        out = torch.full((A.nnz,), float("nan"), dtype=torch.float32, device="cuda")
+        spdl.spdl_sddmm_skewed(A.m, A.k, n, A.nnz, d.ro, d.ci, g.dev(L), g.dev(R), out)
+        torch.cuda.synchronize()
+        g.assert_close(out.cpu().numpy(), ref, S, g.TOL_F32, "sddmm_skewed " + what)
+
+
 # ------------------------------------------------------------------ matrix-core kernels (fp16)
 def _f16(A):
     A.values = A.values.astype(np.float16)
