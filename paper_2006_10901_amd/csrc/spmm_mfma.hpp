@@ -203,9 +203,11 @@ __global__ __launch_bounds__(64 * WAVES * KP) void spmm_mfma_kernel(
           const unsigned rel = (unsigned)(cidx - kc0);
           if (rel < (unsigned)kc) prow[rel] = a;
         }
-        const unsigned long long inside = __builtin_amdgcn_ballot_w64(valid && cidx < kend);
-        before_end += __builtin_popcountll(inside);
-        past = past || __builtin_amdgcn_ballot_w64(valid && cidx >= kend) != 0;
+        if (k > kMfmaChunk) {                            // (one chunk: no cursor to keep)
+          const unsigned long long inside = __builtin_amdgcn_ballot_w64(valid && cidx < kend);
+          before_end += __builtin_popcountll(inside);
+          past = past || __builtin_amdgcn_ballot_w64(valid && cidx >= kend) != 0;
+        }
         below = __builtin_amdgcn_readlane(cidx, 63);
       };
 #pragma unroll

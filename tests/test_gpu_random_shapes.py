@@ -105,7 +105,8 @@ def draw_banded(rng, n):
 def test_random_shapes_entry_points_around_spmm_and_sddmm(g, oracle_lib, stream_seed):
     """The same draw through the other entry points: bias + ReLU epilogue, SDDMM scaled by the
     stored values, SDDMM with the right-hand operand not transposed, fp16 SpMM with 16-bit column
-    indices, the entry points for banded masks on random band / scatter mixes, softmax over rows."""
+    indices, the entry points for banded masks on random band / scatter mixes and those for rows of
+    unequal length, softmax over rows."""
     import torch
     import paper_2006_10901_amd as spdl
     rng = np.random.default_rng(stream_seed)
@@ -117,7 +118,7 @@ def test_random_shapes_entry_points_around_spmm_and_sddmm(g, oracle_lib, stream_
 
     try:
         for it in range(60):
-            op = ("bias_relu", "scaled", "nt", "int16", "banded", "softmax")[int(rng.integers(0, 6))]
+            op = ("bias_relu", "scaled", "nt", "int16", "banded", "softmax", "skewed")[int(rng.integers(0, 7))]
             if op == "banded":
                 n = int(rng.choice([8, 36, 64, 100, 128, 200]))
                 A, seed, kind = draw_banded(rng, n)
@@ -125,7 +126,7 @@ def test_random_shapes_entry_points_around_spmm_and_sddmm(g, oracle_lib, stream_
             else:
                 A, n, seed, f16, kind = draw_case(rng)
             m, k = A.m, A.k
-            f16 = f16 or op == "int16"
+            f16 = (f16 or op == "int16") and op != "skewed"
             A.values = A.values.astype(np.float16 if f16 else np.float32)
             spdl.spdl_force_variant(0, int(rng.integers(0, n_spmm)) if rng.random() < 0.5 else -1)
             spdl.spdl_force_variant(1, int(rng.integers(0, n_sddmm)) if rng.random() < 0.5 else -1)
@@ -137,7 +138,7 @@ def test_random_shapes_entry_points_around_spmm_and_sddmm(g, oracle_lib, stream_
             order = spdl.spdl_build_row_order(m, A.row_offsets) if rng.random() < 0.5 else None
             dorder = None if order is None else g.dev(order)
             a32 = A.values.astype(np.float32)
-            if op in ("bias_relu", "int16", "banded"):
+            if op in ("bias_relu", "int16", "banded", "skewed"):
                 B = wl.dense(k, n, seed + 1, dt)
                 out = fresh((m, n), tdt)
                 if op == "bias_relu":
@@ -153,11 +154,13 @@ def test_random_shapes_entry_points_around_spmm_and_sddmm(g, oracle_lib, stream_
                     if op == "int16":
                         spdl.spdl_spmm_f16_i16(m, k, n, A.nnz, d.ro, g.dev(A.column_indices.astype(np.int16)), d.val,
                                                dorder, g.dev(B), out)
+                    elif op == "skewed":
+                        spdl.spdl_spmm_skewed(m, k, n, A.nnz, d.ro, d.ci, d.val, g.dev(B), out)
                     else:
                         spdl.spdl_spmm_banded(m, k, n, A.nnz, d.ro, d.ci, d.val, g.dev(B), out)
                 torch.cuda.synchronize()
                 g.assert_close(out.cpu().numpy(), C, S, tol, what)
-            if op in ("scaled", "nt", "banded"):
+            if op in ("scaled", "nt", "banded", "skewed"):
                 L, R = wl.dense(m, n, seed + 2, dt), wl.dense(k, n, seed + 3, dt)
                 ref, S = oracle_lib.sddmm(m, k, n, A.row_offsets, A.column_indices, L, R)
                 out = fresh((A.nnz,), tdt)
@@ -171,6 +174,8 @@ def test_random_shapes_entry_points_around_spmm_and_sddmm(g, oracle_lib, stream_
                     fn = spdl.spdl_sddmm_nt_f16 if f16 else spdl.spdl_sddmm_nt
                     fn(m, k, n, A.nnz, d.ro, d.ci, d.val if scaled else None, g.dev(L), g.dev(np.ascontiguousarray(R.T)), out)
                     v = A.values.astype(np.float64) if scaled else v
+                elif op == "skewed":
+                    spdl.spdl_sddmm_skewed(m, k, n, A.nnz, d.ro, d.ci, g.dev(L), g.dev(R), out)
                 else:
                     spdl.spdl_sddmm_banded(m, k, n, A.nnz, d.ro, d.ci, g.dev(L), g.dev(R), out)
                 torch.cuda.synchronize()
