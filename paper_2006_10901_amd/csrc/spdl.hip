@@ -261,10 +261,13 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
     // kernel pays from 64 * density = 3 on; 16995 x 3895 at 3.2 %, n = 128: 89 us against 62 for
     // row-splitting, 5006 x 2875 at 4.1 %, n = 256: 38 against 26, while the LSTM matrix at 95 %
     // sparsity, 10240 columns, runs 1.4 times faster in it.  Eight tiles or more, scanned once per
-    // slab for several tiles: from 1.8 on; 15161 x 5174 at 2.9 %, n = 1024: 321 us against 413.)
+    // slab for several tiles: from 1.8 on, sixteen or more from 1.3 on; 15161 x 5174 at 2.9 %, n = 1024:
+    // 321 us against 413; 5830 x 4537 at 2.1 %, n = 8192: 998 against 1331.  A B of fewer than 4000 rows
+    // is found in L2 at any width: 4297 x 863 at 2.1 %, n = 2048: 56 us against 32 for row-splitting.)
     const double min_reuse = n <= 32                                          ? 12.0
                              : (n <= 64 || out_tiles < kComputeUnits)         ? 5.0
-                             : (n <= 4 * kSlabTile && k < 8192)               ? 3.0
+                             : (n <= 4 * kSlabTile && k < 8192) || k < 4000   ? 3.0
+                             : n >= 16 * kSlabTile                            ? 1.3
                              : n >= 8 * kSlabTile                             ? 1.8
                                                                               : 2.0;
     // (Dense matrices gain so much from the slab kernel that it pays with most compute units idle:
@@ -575,10 +578,11 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
   if (variant < 0) {
     const double density = (m > 0 && k > 0) ? (double)nnz / ((double)m * (double)k) : 0.0;
     const double reuse = 64.0 * density;
-    const bool fp32_fast = fast_ok && sizeof(T) == 4 && m >= 512 && nnz < (1 << 29) && n < (1 << 21);
+    const bool fp32_any_m = fast_ok && sizeof(T) == 4 && nnz < (1 << 29) && n < (1 << 21);
+    const bool fp32_fast = fp32_any_m && m >= 512;
     if (!fast_ok) {
       variant = kSddmmRowstrip;
-    } else if (n <= 128 || !fp32_fast) {
+    } else if (n <= 128 || !fp32_any_m) {
       // Short dot products gain little from the slabs (a row of R is one or two cache lines) unless
       // the reuse is high, and the nonzero-split kernel does not care how the entries are laid out
       // (a banded attention mask leaves most of a panel's column ranges nearly empty).  65..128
@@ -623,13 +627,20 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
       };
       const double flops = 2.0 * (double)nnz * (double)n;                   // per launch, all passes
       const int passes = (n + 127) / 128;
-      const double t_lane = passes * 9.5 + flops / (rate(lane_rate) * 1e6);   // microseconds
+      // (the rates are those of a full machine: a small matrix gives fewer workgroups than there are
+      // compute units, 760 x 231 at 43 %, n = 2048: 24 workgroups, 193 us in the slab kernel against 67
+      // for the nonzero-split kernel, which spreads over the chip whatever the shape)
+      const SddmmLaneShape lsh = sddmm_lane_shape(m, k, nnz, true);
+      const SddmmSlabShape ssh = sddmm_slab_shape(m, k, n);
+      const double lane_fill = std::min(1.0, (double)lsh.panels * lsh.ksplit / kComputeUnits);
+      const double slab_fill = std::min(1.0, (double)ssh.panels * ssh.ksplit / kComputeUnits);
+      const double t_lane = passes * 9.5 + flops / (rate(lane_rate) * 1e6 * lane_fill);   // microseconds
       // (every panel of 64 rows streams all of R through its compute unit: 8 TB/s over the chip at best)
       const double panels64 = (double)((m + kSdRows - 1) / kSdRows);
-      const double t_slab = 8.0 + std::max(flops / (rate(slab_rate) * 1e6), panels64 * (double)k * (double)n * 4.0 / 8.0e6);
+      const double t_slab = 8.0 + std::max(flops / (rate(slab_rate) * 1e6 * slab_fill), panels64 * (double)k * (double)n * 4.0 / 8.0e6);
       // (a strip of the gather kernel steps through its dot product 64 columns at a time, about 1.1 us
       // of memory latency per step: the floor for small problems)
-      const double t_group = 5.0 + 1.1 * (double)(n / 64) + flops / 7.0e6;
+      const double t_group = 5.0 + 1.1 * (double)(n / 64) + flops / (n < 2048 ? 7.0e6 : 5.5e6);
       variant = (t_lane <= t_slab && t_lane <= t_group) ? kSddmmLane : t_slab <= t_group ? kSddmmSlabDma : kSddmmGroup;
       // (the lane kernel's rate is that of rows of equal length; an R of a few megabytes is gathered from L2)
       skewed_lane = t_lane <= 0.45 * t_group && (double)k * (double)n * 4.0 >= 7.0e6;

@@ -175,7 +175,8 @@ def test_sddmm_selection_for_long_dot_products(spdl):
     assert chosen(1024, 1024, 3136, 0.10) == "slabdma"          # the fp32 conv shape
     assert chosen(1024, 1024, 1024, 0.03) == "slabdma"          # small: never 8 passes of fixed cost
     assert chosen(8192, 10240, 256, 0.005) == "group"
-    assert chosen(300, 1024, 1024, 0.10) == "group"             # too few rows for panels of 64
+    assert chosen(300, 1024, 1024, 0.10) == "slabdma"           # few rows, long dot products: gathers pay 1.1 us per 64 columns
+    assert chosen(760, 231, 2048, 0.43) == "group"              # 24 workgroups of slabs on 256 compute units
 
 
 def test_spmm_selection_of_the_window_kernel(spdl):
