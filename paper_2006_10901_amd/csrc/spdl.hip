@@ -264,8 +264,19 @@ void fill_spmm_info(int m, int k, int n, int nnz, const void* B, const void* C, 
     // slab for several tiles: from 1.8 on, sixteen or more from 1.3 on; 15161 x 5174 at 2.9 %, n = 1024:
     // 321 us against 413; 5830 x 4537 at 2.1 %, n = 8192: 998 against 1331.  A B of fewer than 4000 rows
     // is found in L2 at any width: 4297 x 863 at 2.1 %, n = 2048: 56 us against 32 for row-splitting.)
+    // (One tile per panel: what the slab kernel needs depends on how the panels fill the machine.  Whole
+    // rounds of 256 workgroups, 16384 or 32768 rows: it wins from 64 * density = 2 on, 16384 x 4096 at 4 %,
+    // n = 64: 27 us against 36 for the gathers; a round and a half, 24576 rows: from 3 on; three quarters
+    // of a round, 12288 rows: not before 5.  Square matrices keep 5: an attention mask is square, a banded
+    // one of this density takes twice as long in the slab kernel, and the host cannot tell.)
+    const int64_t narrow_rounds = (out_tiles + kComputeUnits - 1) / kComputeUnits;
+    const double narrow_fill = narrow_rounds > 0 ? (double)out_tiles / (double)(narrow_rounds * kComputeUnits) : 0.0;
+    const double narrow_reuse = (m != k && narrow_fill >= 0.95)                        ? 2.0
+                                : (m != k && narrow_fill >= 0.75 && narrow_rounds >= 2) ? 3.0
+                                                                                        : 5.0;
     const double min_reuse = n <= 32                                          ? 12.0
-                             : (n <= 64 || out_tiles < kComputeUnits)         ? 5.0
+                             : n <= 64                                        ? narrow_reuse
+                             : out_tiles < kComputeUnits                      ? 5.0
                              : (n <= 4 * kSlabTile && k < 8192) || k < 4000   ? 3.0
                              : n >= 16 * kSlabTile                            ? 1.3
                              : n >= 8 * kSlabTile                             ? 1.8

@@ -220,6 +220,12 @@ def test_spmm_selection_of_the_window_kernel(spdl):
     assert chosen(4096, 4096, 64, int(4096 * 4096 * 0.5)) == "slabdma"        # 64 workgroups
     assert chosen(3072, 3072, 128, int(3072 * 3072 * 0.35)) == "slabdma"
     assert chosen(2048, 4096, 64, int(2048 * 4096 * 0.5)) == "window"         # 32 workgroups: too few
+    # one tile per panel: the slab kernel from lower densities where the panels fill whole rounds of the machine
+    assert chosen(16384, 4096, 64, int(16384 * 4096 * 0.04)) == "slabdma"     # 256 panels
+    assert chosen(12288, 4096, 64, int(12288 * 4096 * 0.04)) == "window"      # 192 panels
+    assert chosen(24576, 4096, 64, int(24576 * 4096 * 0.04)) == "window"      # 384 panels: from 64 * density = 3 on
+    assert chosen(24576, 4096, 64, int(24576 * 4096 * 0.05)) == "slabdma"
+    assert chosen(16384, 16384, 64, int(16384 * 16384 * 0.04)) == "window"    # square: could be an attention mask
     assert chosen(4096, 4096, 64, 1678008, eb=2) != "window"
     try:
         spdl.spdl_force_variant(0, 4)
