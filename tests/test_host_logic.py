@@ -194,6 +194,7 @@ def test_spmm_selection_of_the_window_kernel(spdl):
     assert chosen(8192, 8192, 64, int(8192 * 8192 * 0.05)) == "window"        # too sparse for slabs of 64 columns
     assert chosen(8192, 8192, 32, int(8192 * 8192 * 0.05)) == "rowsplit"     # narrow output: gathers
     assert chosen(8192, 8192, 32, int(8192 * 8192 * 0.3)) == "slabdma"
+    assert chosen(8192, 8192, 8, int(8192 * 8192 * 0.3)) == "rowsplit"       # an eighth of a tile's lanes
     assert chosen(4096, 4096, 32, 1678008) == "rowsplit"
     assert chosen(4096, 4096, 128, 1678008) == "slabdma"          # 10 % dense: slabs, in workgroups of 8 waves
     assert chosen(4096, 4096, 128, int(4096 * 4096 * 0.06)) == "window"     # ... too sparse for those
