@@ -1137,7 +1137,7 @@ const char* spdl_status_string(int status) {
   }
 }
 
-int spdl_version(void) { return 130; }
+int spdl_version(void) { return 140; }
 
 }  // extern "C"
 
