@@ -607,7 +607,13 @@ void fill_sddmm_info(int m, int k, int n, int nnz, const void* L, const void* R,
       // 1.25 .. 1.4 times faster than gathering, 8192 x 2048 at 10 %: 18.7 us against 25; with 64
       // panels it has to split A's columns over workgroups and the banded attention mask of 4096
       // rows, also 10 % dense, takes 36 us against 24)
-      const bool slab = fp32_fast && reuse >= 2.0 && (n >= 128 || reuse >= 8.0 || (reuse >= 5.0 && m >= 8192));
+      // (panels that fill whole rounds of one workgroup per compute unit, 16384 or 32768 rows: from 4 on,
+      // 7 .. 26 % faster than gathering there; not for square matrices, which may be attention masks)
+      const int64_t panels64 = (m + kSdRows - 1) / kSdRows;
+      const int64_t rounds64 = (panels64 + kComputeUnits - 1) / kComputeUnits;
+      const bool whole_rounds = m != k && rounds64 > 0 && (double)panels64 >= 0.95 * (double)(rounds64 * kComputeUnits);
+      const bool slab = fp32_fast && reuse >= 2.0 &&
+                        (n >= 128 || reuse >= 8.0 || (reuse >= 5.0 && m >= 8192) || (reuse >= 4.0 && whole_rounds));
       variant = lane ? kSddmmLane : slab ? kSddmmSlabDma : kSddmmGroup;
       // The shape of an attention head (33..64 columns, thousands of rows of a few hundred entries,
       // at most 1/8 dense; paper Sec. "Application: Sparse Transformer"): the window kernel, which is

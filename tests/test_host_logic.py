@@ -253,6 +253,11 @@ def test_sddmm_selection_of_the_window_kernel(spdl):
     assert chosen(8192, 2048, 64, int(8192 * 2048 * 0.1)) == "slabdma"
     assert chosen(16384, 4096, 32, int(16384 * 4096 * 0.1)) == "slabdma"
     assert chosen(8192, 8192, 64, int(8192 * 8192 * 0.05)) == "window"
+    # ... from lower densities where the panels fill whole rounds of the machine (not for square matrices)
+    assert chosen(16384, 4096, 64, int(16384 * 4096 * 0.065)) == "slabdma"
+    assert chosen(16384, 4096, 64, int(16384 * 4096 * 0.05)) != "slabdma"
+    assert chosen(12288, 4096, 64, int(12288 * 4096 * 0.065)) != "slabdma"
+    assert chosen(16384, 16384, 64, int(16384 * 16384 * 0.065)) != "slabdma"
     try:
         spdl.spdl_force_variant(1, 6)
         assert chosen(203, 700, 64, 3000) == "window"
